@@ -1,0 +1,167 @@
+/*
+ * rc.h -- C ABI of the reusable-KV-block search (ReasonCache, Sec. IV-A Stage 2
+ * "Block-Level Distance Filtering" and Sec. IV-B "Zero-Copy KV Sharing").
+ *
+ * Newly written, sealed paged-KV blocks ("query blocks", the blocks B_c of the
+ * current step) are scored layer by layer against the resident blocks of the
+ * cache ("pool blocks", the candidates B_k).  A query block whose best pool
+ * partner clears the reuse threshold is redirected to that partner in the
+ * PagedAttention block table; no KV data is copied.
+ *
+ * Conventions shared by every entry point
+ *   - "DEVICE" pointers are HIP device memory on the current device; "HOST"
+ *     pointers are ordinary host memory.  The caller owns every buffer.  The
+ *     library allocates nothing, frees nothing and never synchronises: all
+ *     work is enqueued on the caller's stream (`hip_stream` is a hipStream_t,
+ *     NULL = the default stream).
+ *   - Arguments are validated on the host before anything is launched; on an
+ *     error the outputs are untouched, the return code says what kind of
+ *     error it was and rc_last_error() returns a description.
+ *   - [L] is a pure batch dimension: every layer is an independent problem
+ *     with its own pool, queries, decisions, block tables and refcounts.
+ *   - KV layout: element (layer l, block b, token t, head h, dim d) of a K (or
+ *     V) tensor sits at  l*layer_stride + ((b*T + t)*H + h)*Dh + d  elements
+ *     from the base pointer.  K and V are separate tensors.  Base pointers and
+ *     layer strides must keep every block 16-byte aligned.
+ *   - Supported shapes: head_dim == 128, block_tokens in {16, 32},
+ *     1 <= n_kv_heads <= 16, dtype fp16 or bf16.
+ */
+#ifndef RC_H_
+#define RC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RC_OK = 0,
+  RC_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned pointer, mismatching descriptors */
+  RC_ERR_UNSUPPORTED = 2, /* shape, dtype or mode outside the supported set                           */
+  RC_ERR_WORKSPACE = 3,   /* workspace missing or smaller than rc_*_workspace_size() asks             */
+  RC_ERR_DEVICE = 4       /* the HIP runtime refused a launch                                         */
+} rc_status;
+
+typedef enum { RC_F16 = 0, RC_BF16 = 1 } rc_dtype;
+
+typedef enum {
+  RC_SCORE_BLOCK = 0,       /* one score per block pair over the flattened [T][H][Dh] tensor   */
+  RC_SCORE_PER_HEAD_ALL = 1 /* score per KV head on its [T][Dh] slice, block score = min over  */
+                            /* heads: a block is shared only if every head clears the threshold */
+} rc_mode;
+
+/* Shape of one K (or V) tensor.  HOST struct, read during the call only. */
+typedef struct {
+  int32_t n_layers;     /* L  */
+  int32_t block_tokens; /* T, the paper's block size d                  */
+  int32_t n_kv_heads;   /* H, the paper's h                             */
+  int32_t head_dim;     /* Dh                                           */
+  int32_t dtype;        /* rc_dtype                                     */
+  int64_t layer_stride; /* elements between layer l and l+1 of a tensor */
+} rc_kv_desc;
+
+/*
+ * Squared L2 norm of every K block and every V block (Sec. IV-A Stage 2, the
+ * norm terms of the squared-distance expansion ||x_c||^2 + ||x_k||^2 - 2 x_c.x_k;
+ * the paper computes them once per block by a single reduction and caches them).
+ *
+ *   k, v            DEVICE, n_blocks blocks per layer in the KV layout above
+ *   k_sqnorm,       DEVICE float, [L][n_blocks] in RC_SCORE_BLOCK mode,
+ *   v_sqnorm        [L][n_blocks][H] in RC_SCORE_PER_HEAD_ALL mode (norm of the head's
+ *                   [T][Dh] slice).  Products are exact in fp32; the sum is an fp32 tree.
+ * n_blocks == 0 is legal and launches nothing.
+ */
+rc_status rc_block_norms(const rc_kv_desc* desc, int32_t mode,
+                         const void* k, const void* v, int64_t n_blocks,
+                         float* k_sqnorm, float* v_sqnorm, void* hip_stream);
+
+/* Bytes of DEVICE workspace rc_match_blocks needs for this problem (0 on bad arguments). */
+size_t rc_match_workspace_size(const rc_kv_desc* qdesc, int32_t mode, int64_t Q, int64_t P);
+
+/*
+ * Score every query block against every live pool block of its layer and pick
+ * the best partner (Sec. IV-A Stage 2: the dot-product term of the expansion
+ * with the cached norms; the sharing decision against a threshold).
+ *
+ * Score of a pair, RC_SCORE_BLOCK:  s = (cos(Kq,Kp) + cos(Vq,Vp)) / 2  on the
+ * flattened tensors, cos = <x,y>/sqrt(|x|^2 |y|^2), defined 0 when a norm is 0.
+ * K and V are normalised separately and averaged, as the paper sums the K and V
+ * distances.  For unit vectors |x-y|^2 = 2 - 2cos, so a cosine threshold tau is
+ * the threshold sqrt(2 - 2 tau) on the normalised Euclidean distance.
+ * RC_SCORE_PER_HEAD_ALL: the same on each head's [T][Dh] slice, then the minimum
+ * over heads.
+ *
+ *   qdesc, pdesc    HOST; must agree in everything but layer_stride
+ *   kq, vq          DEVICE, Q query blocks per layer;  kp, vp: P pool blocks per layer
+ *   q_ksq .. p_vsq  DEVICE float, squared norms as rc_block_norms writes them for `mode`
+ *   pool_live       DEVICE uint8 [L][P], 1 = sealed and referenced (eligible target);
+ *                   dead blocks are skipped by the argmax.  NULL = all live.
+ *   tau             reuse threshold on the score; a query matches iff best_score >= tau
+ *   best_idx        DEVICE int32 [L][Q]: argmax over live pool blocks, lowest index on
+ *                   exact ties; -1 if the layer has no live pool block
+ *   best_score      DEVICE float [L][Q]: its score (-inf if none)
+ *   match_idx       DEVICE int32 [L][Q]: best_idx if best_score >= tau, else -1
+ *   second_score    DEVICE float [L][Q] or NULL: second-largest score over live pool
+ *                   blocks, counted with multiplicity (-inf if fewer than two)
+ *   workspace       DEVICE, >= rc_match_workspace_size() bytes, 16-byte aligned; contents
+ *                   are scratch.  Calls that share a workspace must not overlap.
+ * Accumulation is fp32 on the matrix cores, the epilogue is fp32.  Q == 0 launches
+ * nothing; P == 0 writes -1 / -inf.
+ */
+rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_t mode,
+                          const void* kq, const void* vq, int64_t Q,
+                          const float* q_ksq, const float* q_vsq,
+                          const void* kp, const void* vp, int64_t P,
+                          const float* p_ksq, const float* p_vsq,
+                          const uint8_t* pool_live, float tau,
+                          int32_t* best_idx, float* best_score, int32_t* match_idx,
+                          float* second_score,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of DEVICE workspace rc_remap_block_table needs (0 on bad arguments). */
+size_t rc_remap_workspace_size(int32_t n_layers, int64_t R, int64_t E, int64_t Q, int64_t NB);
+
+/*
+ * Apply the sharing decisions to the block tables without copying KV data
+ * (Sec. IV-B: sharing raises the kept block's reference count and rewrites the
+ * block-table entry; a block returns to the free pool only at reference count 0).
+ * The resident pool block survives, the new query block is released; pool blocks
+ * are never redirected, so there are no redirect chains.
+ *
+ * Per layer l:  every table entry equal to query_ids[q] with match_idx[l][q] = m >= 0
+ * becomes target(m) = pool_ids ? pool_ids[m] : m.  With cnt[q] the number of such
+ * entries:  refcount[target(m)] += cnt[q],  refcount[query_ids[q]] -= cnt[q],
+ * freed[l][q] = 1 iff q matched and its refcount reached 0.  All other entries and
+ * refcounts are copied unchanged.  n_remapped[l] = number of entries rewritten.
+ *
+ *   tables_in/out   DEVICE int32 [L][R][E]; tables_out may be tables_in (in place).
+ *                   Entries outside [0, NB) (e.g. -1 padding) pass through unchanged.
+ *   query_ids       DEVICE int32 [Q], distinct physical block ids in [0, NB), same for all layers
+ *   pool_ids        DEVICE int32 [P] physical ids in [0, NB), disjoint from query_ids; NULL = identity (then P <= NB)
+ *   match_idx       DEVICE int32 [L][Q], values in [-1, P) (others are treated as -1)
+ *   refcount_in/out DEVICE int32 [L][NB]; refcount_out may be refcount_in
+ *   freed           DEVICE uint8 [L][Q];  n_remapped: DEVICE int32 [L]
+ *   workspace       DEVICE, >= rc_remap_workspace_size() bytes, 16-byte aligned
+ * No atomics are used: the result is the same on every run.  Q is limited to 16384.
+ */
+rc_status rc_remap_block_table(int32_t n_layers,
+                               const int32_t* tables_in, int32_t* tables_out,
+                               int64_t R, int64_t E,
+                               const int32_t* query_ids, const int32_t* pool_ids,
+                               const int32_t* match_idx, int64_t Q, int64_t P, int64_t NB,
+                               const int32_t* refcount_in, int32_t* refcount_out,
+                               uint8_t* freed, int32_t* n_remapped,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* HOST string describing the calling thread's last error ("" if none). Never NULL. */
+const char* rc_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t rc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RC_H_ */

@@ -1,0 +1,339 @@
+/*
+ * rc_oracle.c -- plain CPU statement of the reusable-KV-block search.
+ *
+ * TEST INFRASTRUCTURE, not product code: only the tests, the smoke check and the
+ * CPU-baseline leg of the benchmark may call this.  It shares nothing with the
+ * HIP path.  Everything is the definition written out in double precision on the
+ * exact fp16/bf16 bit patterns the GPU sees; the only parallelism is an OpenMP
+ * loop over independent pool blocks.
+ *
+ * What is computed (ReasonCache Sec. IV-A Stage 2 and Sec. IV-B):
+ *   - squared L2 norm of a flattened K or V block (the cached terms of the
+ *     squared-distance expansion of Stage 2);
+ *   - pair score s = (cos(Kq,Kp) + cos(Vq,Vp))/2, cos = <x,y>/sqrt(|x|^2|y|^2),
+ *     cos := 0 when a norm is 0.  K and V are normalised separately and averaged,
+ *     mirroring the paper's sum of the K distance and the V distance.  For unit
+ *     vectors |x-y|^2 = 2 - 2cos, which ties the score to the paper's distance;
+ *   - per-head-all mode: the same on each head's [T][Dh] slice, then min over heads;
+ *   - best live pool block per query (lowest index on exact ties), runner-up
+ *     value, match iff best >= tau (the Stage 2 sharing decision);
+ *   - block-table remap with reference counts (Sec. IV-B).
+ *
+ * Pins (tests/test_oracle_pins.py): bit decode against two library decoders,
+ * integer closed forms for norms, the direct subtract-and-square distance against
+ * the expansion, planted duplicates (score exactly 1), disjoint supports (score
+ * exactly 0), K/V-averaging and per-head constructions with hand-known values,
+ * the 1/sqrt(1+sigma^2) law for noisy copies, tie/dead/threshold cases, and for the
+ * remap a hand-worked table plus conservation/idempotence invariants.
+ * Every function here is pinned; none is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_F16 = 0, ORC_BF16 = 1 };
+enum { ORC_BLOCK = 0, ORC_PER_HEAD_ALL = 1 };
+
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+static double decode_f16(uint16_t b) {
+  int sign = b >> 15, e = (b >> 10) & 31, m = b & 1023;
+  double v;
+  if (e == 0)
+    v = ldexp((double)m, -24); /* subnormal: m * 2^-10 * 2^-14 */
+  else if (e == 31)
+    v = m ? NAN : INFINITY;
+  else
+    v = ldexp((double)(1024 + m), e - 25); /* (1 + m/1024) * 2^(e-15) */
+  return sign ? -v : v;
+}
+
+/* bfloat16 is the upper half of an IEEE binary32. */
+static double decode_bf16(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+static double decode(int dtype, uint16_t b) { return dtype == ORC_BF16 ? decode_bf16(b) : decode_f16(b); }
+
+static void decode_block(int dtype, const uint16_t* bits, int64_t n, double* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = decode(dtype, bits[i]);
+}
+
+int rc_oracle_decode(int dtype, const uint16_t* bits, int64_t n, double* out) {
+  if (!bits || !out || n < 0) return 1;
+  decode_block(dtype, bits, n, out);
+  return 0;
+}
+
+/* Index of (token t, head h, dim d) inside one block laid out [T][H][Dh]. */
+static int64_t at(int H, int Dh, int t, int h, int d) { return ((int64_t)t * H + h) * Dh + d; }
+
+/* Sum of squares over the whole block (head < 0) or over one head's [T][Dh] slice. */
+static double sqnorm(const double* x, int T, int H, int Dh, int head) {
+  double acc = 0.0;
+  for (int t = 0; t < T; ++t)
+    for (int h = 0; h < H; ++h) {
+      if (head >= 0 && h != head) continue;
+      for (int d = 0; d < Dh; ++d) {
+        double a = x[at(H, Dh, t, h, d)];
+        acc += a * a;
+      }
+    }
+  return acc;
+}
+
+static double dot(const double* x, const double* y, int T, int H, int Dh, int head) {
+  double acc = 0.0;
+  for (int t = 0; t < T; ++t)
+    for (int h = 0; h < H; ++h) {
+      if (head >= 0 && h != head) continue;
+      for (int d = 0; d < Dh; ++d) acc += x[at(H, Dh, t, h, d)] * y[at(H, Dh, t, h, d)];
+    }
+  return acc;
+}
+
+static double cosine(double xy, double xx, double yy) {
+  if (xx == 0.0 || yy == 0.0) return 0.0;
+  return xy / sqrt(xx * yy);
+}
+
+/* Score of one pair from decoded blocks; norms are recomputed here, by definition. */
+static double pair_score(const double* kq, const double* vq, const double* kp, const double* vp,
+                         int T, int H, int Dh, int mode) {
+  if (mode == ORC_BLOCK) {
+    double ck = cosine(dot(kq, kp, T, H, Dh, -1), sqnorm(kq, T, H, Dh, -1), sqnorm(kp, T, H, Dh, -1));
+    double cv = cosine(dot(vq, vp, T, H, Dh, -1), sqnorm(vq, T, H, Dh, -1), sqnorm(vp, T, H, Dh, -1));
+    return 0.5 * (ck + cv);
+  }
+  double s = INFINITY;
+  for (int h = 0; h < H; ++h) {
+    double ck = cosine(dot(kq, kp, T, H, Dh, h), sqnorm(kq, T, H, Dh, h), sqnorm(kp, T, H, Dh, h));
+    double cv = cosine(dot(vq, vp, T, H, Dh, h), sqnorm(vq, T, H, Dh, h), sqnorm(vp, T, H, Dh, h));
+    double sh = 0.5 * (ck + cv);
+    if (sh < s) s = sh;
+  }
+  return s;
+}
+
+static int bad_shape(int L, int T, int H, int Dh, int64_t layer_stride, int64_t n) {
+  return L < 0 || T <= 0 || H <= 0 || Dh <= 0 || n < 0 || layer_stride < n * (int64_t)T * H * Dh;
+}
+
+/* ksq, vsq: [L][n] (block mode) or [L][n][H] (per-head-all mode), double. */
+int rc_oracle_block_norms(int dtype, int mode, int L, int T, int H, int Dh, int64_t layer_stride,
+                          const uint16_t* k, const uint16_t* v, int64_t n, double* ksq, double* vsq) {
+  if (bad_shape(L, T, H, Dh, layer_stride, n) || !ksq || !vsq || (n > 0 && L > 0 && (!k || !v))) return 1;
+  const int64_t D = (int64_t)T * H * Dh;
+  double* x = (double*)malloc(sizeof(double) * (size_t)(D > 0 ? D : 1));
+  if (!x) return 2;
+  for (int l = 0; l < L; ++l)
+    for (int64_t b = 0; b < n; ++b)
+      for (int which = 0; which < 2; ++which) {
+        const uint16_t* src = (which ? v : k) + (int64_t)l * layer_stride + b * D;
+        double* dst = which ? vsq : ksq;
+        decode_block(dtype, src, D, x);
+        if (mode == ORC_BLOCK)
+          dst[(int64_t)l * n + b] = sqnorm(x, T, H, Dh, -1);
+        else
+          for (int h = 0; h < H; ++h) dst[((int64_t)l * n + b) * H + h] = sqnorm(x, T, H, Dh, h);
+      }
+  free(x);
+  return 0;
+}
+
+/* Squared Euclidean distance by subtracting and squaring (the left side of the
+ * Stage 2 expansion); used by the pins and by nothing else. */
+int rc_oracle_sqdist(int dtype, const uint16_t* x, const uint16_t* y, int64_t n, double* out) {
+  if (!x || !y || !out || n < 0) return 1;
+  double acc = 0.0;
+  for (int64_t i = 0; i < n; ++i) {
+    double d = decode(dtype, x[i]) - decode(dtype, y[i]);
+    acc += d * d;
+  }
+  *out = acc;
+  return 0;
+}
+
+/* Scores of listed pairs, each from scratch: out[i] = s(layer li[i], query qi[i], pool pi[i]). */
+int rc_oracle_score_pairs(int dtype, int mode, int T, int H, int Dh,
+                          const uint16_t* kq, const uint16_t* vq, int64_t q_layer_stride,
+                          const uint16_t* kp, const uint16_t* vp, int64_t p_layer_stride,
+                          int64_t n_pairs, const int32_t* li, const int32_t* qi, const int32_t* pi,
+                          double* out) {
+  if (T <= 0 || H <= 0 || Dh <= 0 || n_pairs < 0 || !out) return 1;
+  if (n_pairs > 0 && (!kq || !vq || !kp || !vp || !li || !qi || !pi)) return 1;
+  const int64_t D = (int64_t)T * H * Dh;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t i = 0; i < n_pairs; ++i) {
+    double* buf = (double*)malloc(sizeof(double) * 4 * (size_t)D);
+    if (!buf) { err = 2; continue; }
+    decode_block(dtype, kq + (int64_t)li[i] * q_layer_stride + (int64_t)qi[i] * D, D, buf);
+    decode_block(dtype, vq + (int64_t)li[i] * q_layer_stride + (int64_t)qi[i] * D, D, buf + D);
+    decode_block(dtype, kp + (int64_t)li[i] * p_layer_stride + (int64_t)pi[i] * D, D, buf + 2 * D);
+    decode_block(dtype, vp + (int64_t)li[i] * p_layer_stride + (int64_t)pi[i] * D, D, buf + 3 * D);
+    out[i] = pair_score(buf, buf + D, buf + 2 * D, buf + 3 * D, T, H, Dh, mode);
+    free(buf);
+  }
+  return err;
+}
+
+/*
+ * Exhaustive search, one layer after the other.
+ *   scores_out   optional [L][Q][P] double, the full score matrix (dead blocks included)
+ *   best_idx     [L][Q] argmax over live pool blocks, lowest index on exact ties, -1 if none
+ *   best_score   [L][Q] its score (-inf if none)
+ *   match_idx    [L][Q] best_idx if best_score >= tau else -1
+ *   second_score [L][Q] second-largest live score counted with multiplicity (-inf if < 2 live)
+ * The squared norms of a block are computed once and reused for every pair it
+ * takes part in (the paper's norm caching); sums run in index order.
+ */
+int rc_oracle_match(int dtype, int mode, int L, int T, int H, int Dh,
+                    const uint16_t* kq, const uint16_t* vq, int64_t q_layer_stride, int64_t Q,
+                    const uint16_t* kp, const uint16_t* vp, int64_t p_layer_stride, int64_t P,
+                    const uint8_t* live, double tau,
+                    int32_t* best_idx, double* best_score, int32_t* match_idx, double* second_score,
+                    double* scores_out) {
+  if (bad_shape(L, T, H, Dh, q_layer_stride, Q) || bad_shape(L, T, H, Dh, p_layer_stride, P)) return 1;
+  if (!best_idx || !best_score || !match_idx || !second_score) return 1;
+  if (L > 0 && Q > 0 && (!kq || !vq)) return 1;
+  if (L > 0 && P > 0 && (!kp || !vp)) return 1;
+  const int64_t D = (int64_t)T * H * Dh;
+  const int NH = (mode == ORC_BLOCK) ? 1 : H; /* norm slots per block */
+  int err = 0;
+
+  double* qk = (double*)malloc(sizeof(double) * (size_t)(Q * D + 1));
+  double* qv = (double*)malloc(sizeof(double) * (size_t)(Q * D + 1));
+  double* qkn = (double*)malloc(sizeof(double) * (size_t)(Q * NH + 1));
+  double* qvn = (double*)malloc(sizeof(double) * (size_t)(Q * NH + 1));
+  double* S = (double*)malloc(sizeof(double) * (size_t)(Q * P + 1));
+  if (!qk || !qv || !qkn || !qvn || !S) { err = 2; goto done; }
+
+  for (int l = 0; l < L; ++l) {
+    for (int64_t q = 0; q < Q; ++q) {
+      decode_block(dtype, kq + (int64_t)l * q_layer_stride + q * D, D, qk + q * D);
+      decode_block(dtype, vq + (int64_t)l * q_layer_stride + q * D, D, qv + q * D);
+      for (int h = 0; h < NH; ++h) {
+        int head = (mode == ORC_BLOCK) ? -1 : h;
+        qkn[q * NH + h] = sqnorm(qk + q * D, T, H, Dh, head);
+        qvn[q * NH + h] = sqnorm(qv + q * D, T, H, Dh, head);
+      }
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t p = 0; p < P; ++p) {
+      double* pk = (double*)malloc(sizeof(double) * 2 * (size_t)D);
+      if (!pk) { err = 2; continue; }
+      double* pv = pk + D;
+      double pkn[64], pvn[64];
+      decode_block(dtype, kp + (int64_t)l * p_layer_stride + p * D, D, pk);
+      decode_block(dtype, vp + (int64_t)l * p_layer_stride + p * D, D, pv);
+      for (int h = 0; h < NH; ++h) {
+        int head = (mode == ORC_BLOCK) ? -1 : h;
+        pkn[h] = sqnorm(pk, T, H, Dh, head);
+        pvn[h] = sqnorm(pv, T, H, Dh, head);
+      }
+      for (int64_t q = 0; q < Q; ++q) {
+        double s;
+        if (mode == ORC_BLOCK) {
+          double ck = cosine(dot(qk + q * D, pk, T, H, Dh, -1), qkn[q], pkn[0]);
+          double cv = cosine(dot(qv + q * D, pv, T, H, Dh, -1), qvn[q], pvn[0]);
+          s = 0.5 * (ck + cv);
+        } else {
+          s = INFINITY;
+          for (int h = 0; h < H; ++h) {
+            double ck = cosine(dot(qk + q * D, pk, T, H, Dh, h), qkn[q * NH + h], pkn[h]);
+            double cv = cosine(dot(qv + q * D, pv, T, H, Dh, h), qvn[q * NH + h], pvn[h]);
+            double sh = 0.5 * (ck + cv);
+            if (sh < s) s = sh;
+          }
+        }
+        S[q * P + p] = s;
+      }
+      free(pk);
+    }
+    if (err) goto done;
+    for (int64_t q = 0; q < Q; ++q) {
+      int32_t bi = -1;
+      double bs = -INFINITY, ss = -INFINITY;
+      for (int64_t p = 0; p < P; ++p) {
+        if (live && !live[(int64_t)l * P + p]) continue;
+        double s = S[q * P + p];
+        if (s > bs) { ss = bs; bs = s; bi = (int32_t)p; }
+        else if (s > ss) ss = s;
+      }
+      best_idx[(int64_t)l * Q + q] = bi;
+      best_score[(int64_t)l * Q + q] = bs;
+      second_score[(int64_t)l * Q + q] = ss;
+      match_idx[(int64_t)l * Q + q] = (bi >= 0 && bs >= tau) ? bi : -1;
+    }
+    if (scores_out) memcpy(scores_out + (int64_t)l * Q * P, S, sizeof(double) * (size_t)(Q * P));
+  }
+done:
+  free(qk); free(qv); free(qkn); free(qvn); free(S);
+  return err;
+}
+
+/*
+ * Block-table remap with reference counts (Sec. IV-B), per layer:
+ *   redirect = identity on [0, NB); redirect[query_ids[q]] = target(match_idx[q]) for matched q,
+ *   target(m) = pool_ids ? pool_ids[m] : m;
+ *   tables_out[e] = redirect[tables_in[e]] for entries in [0, NB), other entries pass through;
+ *   cnt[b] = number of entries of tables_in equal to b;
+ *   for matched q (b = query_ids[q], m its target): rc[m] += cnt[b]; rc[b] -= cnt[b];
+ *   freed[q] = (rc[b] == 0);   n_remapped = number of entries whose value changed.
+ * tables_out / refcount_out may alias their inputs.
+ */
+int rc_oracle_remap(int L, const int32_t* tables_in, int32_t* tables_out, int64_t R, int64_t E,
+                    const int32_t* query_ids, const int32_t* pool_ids, const int32_t* match_idx,
+                    int64_t Q, int64_t P, int64_t NB,
+                    const int32_t* refcount_in, int32_t* refcount_out,
+                    uint8_t* freed, int32_t* n_remapped) {
+  if (L < 0 || R < 0 || E < 0 || Q < 0 || P < 0 || NB < 0) return 1;
+  if (L > 0 && (!n_remapped || (R * E > 0 && (!tables_in || !tables_out)) ||
+                (NB > 0 && (!refcount_in || !refcount_out)) || (Q > 0 && (!query_ids || !match_idx || !freed))))
+    return 1;
+  for (int64_t q = 0; q < Q; ++q)
+    if (query_ids[q] < 0 || query_ids[q] >= NB) return 1;
+  for (int64_t p = 0; pool_ids && p < P; ++p)
+    if (pool_ids[p] < 0 || pool_ids[p] >= NB) return 1;
+  if (!pool_ids && P > NB) return 1;
+  int32_t* redirect = (int32_t*)malloc(sizeof(int32_t) * (size_t)(NB + 1));
+  int64_t* cnt = (int64_t*)malloc(sizeof(int64_t) * (size_t)(NB + 1));
+  if (!redirect || !cnt) { free(redirect); free(cnt); return 2; }
+  for (int l = 0; l < L; ++l) {
+    const int32_t* tin = tables_in + (int64_t)l * R * E;
+    int32_t* tout = tables_out + (int64_t)l * R * E;
+    const int32_t* m = match_idx + (int64_t)l * Q;
+    for (int64_t b = 0; b < NB; ++b) { redirect[b] = (int32_t)b; cnt[b] = 0; }
+    for (int64_t q = 0; q < Q; ++q)
+      if (m[q] >= 0 && m[q] < P) redirect[query_ids[q]] = pool_ids ? pool_ids[m[q]] : m[q];
+    int32_t changed = 0;
+    for (int64_t e = 0; e < R * E; ++e) {
+      int32_t b = tin[e];
+      if (b >= 0 && b < NB) {
+        cnt[b] += 1;
+        if (redirect[b] != b) changed += 1;
+        tout[e] = redirect[b];
+      } else {
+        tout[e] = b;
+      }
+    }
+    for (int64_t b = 0; b < NB; ++b) refcount_out[(int64_t)l * NB + b] = refcount_in[(int64_t)l * NB + b];
+    for (int64_t q = 0; q < Q; ++q) {
+      freed[(int64_t)l * Q + q] = 0;
+      if (m[q] < 0 || m[q] >= P) continue;
+      int32_t b = query_ids[q], tgt = redirect[b];
+      refcount_out[(int64_t)l * NB + tgt] += (int32_t)cnt[b];
+      refcount_out[(int64_t)l * NB + b] -= (int32_t)cnt[b];
+    }
+    for (int64_t q = 0; q < Q; ++q)
+      if (m[q] >= 0 && m[q] < P) freed[(int64_t)l * Q + q] = (refcount_out[(int64_t)l * NB + query_ids[q]] == 0);
+    n_remapped[l] = changed;
+  }
+  free(redirect);
+  free(cnt);
+  return 0;
+}

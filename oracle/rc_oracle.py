@@ -1,0 +1,173 @@
+"""ctypes front end of the CPU oracle (``rc_oracle.c``).
+
+TEST INFRASTRUCTURE, not product code: only ``tests/``, the smoke check and the
+CPU-baseline leg of ``bench.py`` may import this module.  It shares nothing with
+the HIP path and never imports it.
+
+KV tensors are passed as numpy ``uint16`` arrays holding the raw fp16 / bf16 bit
+patterns, shaped ``[L][n][T][H][Dh]`` and C-contiguous.  All results are double
+precision / int32 numpy arrays.  What each function computes, and the passages
+of the paper it follows, is stated in ``rc_oracle.c``.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rc_oracle.c")
+_LIB = os.path.join(_HERE, "librc_oracle.so")
+
+F16, BF16 = 0, 1
+BLOCK, PER_HEAD_ALL = 0, 1
+
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain -O2, OpenMP over independent blocks)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _kv(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16 and a.ndim == 5, "KV must be uint16 bits shaped [L][n][T][H][Dh]"
+    return a
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def n_threads():
+    """OpenMP threads the oracle's parallel loops will use."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        return int(env.split(",")[0])
+    return len(os.sched_getaffinity(0))
+
+
+def decode(dtype, bits):
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float64)
+    _check(_load().rc_oracle_decode(ctypes.c_int(dtype), _p(bits), ctypes.c_int64(bits.size), _p(out)), "decode")
+    return out
+
+
+def block_norms(dtype, mode, k, v):
+    """Squared norms -> (ksq, vsq), each [L][n] (BLOCK) or [L][n][H] (PER_HEAD_ALL)."""
+    k, v = _kv(k), _kv(v)
+    assert k.shape == v.shape
+    L, n, T, H, Dh = k.shape
+    shape = (L, n) if mode == BLOCK else (L, n, H)
+    ksq = np.zeros(shape, dtype=np.float64)
+    vsq = np.zeros(shape, dtype=np.float64)
+    rc = _load().rc_oracle_block_norms(
+        ctypes.c_int(dtype), ctypes.c_int(mode), ctypes.c_int(L), ctypes.c_int(T), ctypes.c_int(H),
+        ctypes.c_int(Dh), ctypes.c_int64(n * T * H * Dh), _p(k), _p(v), ctypes.c_int64(n), _p(ksq), _p(vsq))
+    _check(rc, "block_norms")
+    return ksq, vsq
+
+
+def sqdist(dtype, x, y):
+    """Sum of (x-y)^2 over two equally sized bit arrays, by subtracting and squaring."""
+    x = np.ascontiguousarray(x, dtype=np.uint16).ravel()
+    y = np.ascontiguousarray(y, dtype=np.uint16).ravel()
+    assert x.size == y.size
+    out = ctypes.c_double(0.0)
+    _check(_load().rc_oracle_sqdist(ctypes.c_int(dtype), _p(x), _p(y), ctypes.c_int64(x.size), ctypes.byref(out)),
+           "sqdist")
+    return out.value
+
+
+def score_pairs(dtype, mode, kq, vq, kp, vp, li, qi, pi):
+    """Scores of the listed (layer, query, pool) triples, each computed from scratch."""
+    kq, vq, kp, vp = _kv(kq), _kv(vq), _kv(kp), _kv(vp)
+    L, Q, T, H, Dh = kq.shape
+    P = kp.shape[1]
+    li = np.ascontiguousarray(li, dtype=np.int32)
+    qi = np.ascontiguousarray(qi, dtype=np.int32)
+    pi = np.ascontiguousarray(pi, dtype=np.int32)
+    assert li.shape == qi.shape == pi.shape
+    assert (li >= 0).all() and (li < L).all() and (qi >= 0).all() and (qi < Q).all()
+    assert (pi >= 0).all() and (pi < P).all()
+    out = np.zeros(li.shape, dtype=np.float64)
+    D = T * H * Dh
+    rc = _load().rc_oracle_score_pairs(
+        ctypes.c_int(dtype), ctypes.c_int(mode), ctypes.c_int(T), ctypes.c_int(H), ctypes.c_int(Dh),
+        _p(kq), _p(vq), ctypes.c_int64(Q * D), _p(kp), _p(vp), ctypes.c_int64(P * D),
+        ctypes.c_int64(li.size), _p(li), _p(qi), _p(pi), _p(out))
+    _check(rc, "score_pairs")
+    return out
+
+
+def match(dtype, mode, kq, vq, kp, vp, live, tau, want_scores=False):
+    """Exhaustive search.  Returns dict(best_idx, best_score, match_idx, second_score[, scores])."""
+    kq, vq, kp, vp = _kv(kq), _kv(vq), _kv(kp), _kv(vp)
+    L, Q, T, H, Dh = kq.shape
+    P = kp.shape[1]
+    assert vq.shape == kq.shape and vp.shape == kp.shape and kp.shape[0] == L and kp.shape[2:] == kq.shape[2:]
+    if live is not None:
+        live = np.ascontiguousarray(live, dtype=np.uint8)
+        assert live.shape == (L, P)
+    D = T * H * Dh
+    best_idx = np.zeros((L, Q), dtype=np.int32)
+    match_idx = np.zeros((L, Q), dtype=np.int32)
+    best_score = np.zeros((L, Q), dtype=np.float64)
+    second = np.zeros((L, Q), dtype=np.float64)
+    scores = np.zeros((L, Q, P), dtype=np.float64) if want_scores else None
+    rc = _load().rc_oracle_match(
+        ctypes.c_int(dtype), ctypes.c_int(mode), ctypes.c_int(L), ctypes.c_int(T), ctypes.c_int(H), ctypes.c_int(Dh),
+        _p(kq), _p(vq), ctypes.c_int64(Q * D), ctypes.c_int64(Q),
+        _p(kp), _p(vp), ctypes.c_int64(P * D), ctypes.c_int64(P),
+        _p(live), ctypes.c_double(tau),
+        _p(best_idx), _p(best_score), _p(match_idx), _p(second), _p(scores))
+    _check(rc, "match")
+    out = dict(best_idx=best_idx, best_score=best_score, match_idx=match_idx, second_score=second)
+    if want_scores:
+        out["scores"] = scores
+    return out
+
+
+def remap(tables, query_ids, pool_ids, match_idx, P, NB, refcount):
+    """Block-table remap.  Returns dict(tables, refcount, freed, n_remapped); inputs are not modified."""
+    tables = np.ascontiguousarray(tables, dtype=np.int32)
+    assert tables.ndim == 3
+    L, R, E = tables.shape
+    query_ids = np.ascontiguousarray(query_ids, dtype=np.int32)
+    Q = query_ids.size
+    match_idx = np.ascontiguousarray(match_idx, dtype=np.int32)
+    assert match_idx.shape == (L, Q)
+    if pool_ids is not None:
+        pool_ids = np.ascontiguousarray(pool_ids, dtype=np.int32)
+        assert pool_ids.size == P
+    refcount = np.ascontiguousarray(refcount, dtype=np.int32)
+    assert refcount.shape == (L, NB)
+    tout = np.empty_like(tables)
+    rout = np.empty_like(refcount)
+    freed = np.zeros((L, Q), dtype=np.uint8)
+    nrem = np.zeros((L,), dtype=np.int32)
+    rc = _load().rc_oracle_remap(
+        ctypes.c_int(L), _p(tables), _p(tout), ctypes.c_int64(R), ctypes.c_int64(E),
+        _p(query_ids), _p(pool_ids), _p(match_idx), ctypes.c_int64(Q), ctypes.c_int64(P), ctypes.c_int64(NB),
+        _p(refcount), _p(rout), _p(freed), _p(nrem))
+    _check(rc, "remap")
+    return dict(tables=tout, refcount=rout, freed=freed, n_remapped=nrem)

@@ -1,0 +1,335 @@
+"""Pins of the CPU oracle against things that are not the oracle.
+
+Each test fixes the oracle to a fact the paper or plain mathematics determines:
+library bit decoders, integer closed forms, the squared-distance expansion of
+Sec. IV-A Stage 2, hand-worked pairs and tables (tests/golden), statistical laws
+of the synthetic workloads, and brute force written with a different formula.
+No GPU is involved.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_21433_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def enc(x, dtype):
+    """float array -> uint16 bit patterns through a library encoder (numpy fp16 / torch bf16)."""
+    x = np.asarray(x, dtype=np.float32)
+    if dtype == 0:
+        return x.astype(np.float16).view(np.uint16)
+    return torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def dec(bits, dtype):
+    """uint16 bit patterns -> float64 through a library decoder."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    if dtype == 0:
+        return bits.view(np.float16).astype(np.float64)
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+
+
+def blk(x, T, H, Dh, dtype):
+    """1 layer, n blocks: [n][D] floats -> [1][n][T][H][Dh] bits."""
+    x = np.asarray(x, dtype=np.float32)
+    return enc(x, dtype).reshape(1, -1, T, H, Dh)
+
+
+# ---------------------------------------------------------------- decoding
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_decode_all_bit_patterns(oracle, dtype):
+    bits = np.arange(65536, dtype=np.uint16)
+    mine = oracle.decode(dtype, bits)
+    ref = dec(bits, dtype)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(mine), nan)
+    assert np.array_equal(mine[~nan], ref[~nan])
+    assert np.array_equal(np.signbit(mine[~nan]), np.signbit(ref[~nan]))
+
+
+# ---------------------------------------------------------------- norms
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_norm_integer_closed_form(oracle, dtype):
+    # 1..16 -> sum of squares n(n+1)(2n+1)/6 = 1496; ones -> D; a single 3 -> 9.
+    T, H, Dh = 2, 2, 4
+    D = T * H * Dh
+    x = np.stack([np.arange(1, D + 1), np.ones(D), np.eye(D)[5] * 3.0, np.zeros(D)])
+    k = blk(x, T, H, Dh, dtype)
+    v = blk(2 * x, T, H, Dh, dtype)
+    ksq, vsq = oracle.block_norms(dtype, oracle.BLOCK, k, v)
+    assert ksq.tolist() == [[1496.0, 16.0, 9.0, 0.0]]
+    assert vsq.tolist() == [[4 * 1496.0, 64.0, 36.0, 0.0]]
+
+
+def test_norm_per_head_slices_and_layers(oracle):
+    # Head h of a [T][H][Dh] block is x[:, h, :]; checked with numpy's own reshape on two layers.
+    rng = np.random.RandomState(5)
+    L, n, T, H, Dh = 2, 3, 4, 3, 8
+    x = rng.randint(-8, 9, size=(L, n, T, H, Dh)).astype(np.float32)
+    y = rng.randint(-8, 9, size=(L, n, T, H, Dh)).astype(np.float32)
+    ksq, vsq = oracle.block_norms(0, oracle.PER_HEAD_ALL, enc(x, 0), enc(y, 0))
+    assert ksq.shape == (L, n, H)
+    assert np.array_equal(ksq, (x.astype(np.float64) ** 2).sum(axis=(2, 4)))
+    assert np.array_equal(vsq, (y.astype(np.float64) ** 2).sum(axis=(2, 4)))
+    kb, vb = oracle.block_norms(0, oracle.BLOCK, enc(x, 0), enc(y, 0))
+    assert np.array_equal(kb, ksq.sum(axis=2)) and np.array_equal(vb, vsq.sum(axis=2))
+
+
+# ---------------------------------------------------------------- pair scores
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_golden_pairs(oracle, dtype):
+    cases = json.load(open(os.path.join(GOLD, "pair_scores_handworked.json")))["cases"]
+    for c in cases:
+        T, H, Dh = c["T"], c["H"], c["Dh"]
+        a = [blk([c[n]], T, H, Dh, dtype) for n in ("kq", "vq", "kp", "vp")]
+        z = np.zeros(1, dtype=np.int32)
+        s_block = oracle.score_pairs(dtype, oracle.BLOCK, *a, z, z, z)[0]
+        s_head = oracle.score_pairs(dtype, oracle.PER_HEAD_ALL, *a, z, z, z)[0]
+        assert s_block == pytest.approx(c["block"], abs=1e-14), c["name"]
+        assert s_head == pytest.approx(c["per_head"], abs=1e-14), c["name"]
+        # the search must report the same numbers as the from-scratch pair routine
+        for mode, want in ((oracle.BLOCK, c["block"]), (oracle.PER_HEAD_ALL, c["per_head"])):
+            r = oracle.match(dtype, mode, a[0], a[1], a[2], a[3], None, -10.0, want_scores=True)
+            assert r["scores"][0, 0, 0] == pytest.approx(want, abs=1e-14)
+            assert r["best_score"][0, 0] == pytest.approx(want, abs=1e-14)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_expansion_identity_vs_direct_distance(oracle, dtype):
+    # |x-y|^2 computed by subtracting and squaring must equal |x|^2 + |y|^2 - 2 x.y  (Stage 2 expansion),
+    # with x.y recovered from the oracle's cosine.  V is a copy (cos 1) so s = (cosK + 1)/2.
+    rng = np.random.RandomState(11)
+    T, H, Dh = 2, 2, 4
+    D = T * H * Dh
+    for _ in range(20):
+        x = enc(rng.randn(D), dtype)
+        y = enc(rng.randn(D), dtype)
+        kq, kp = x.reshape(1, 1, T, H, Dh), y.reshape(1, 1, T, H, Dh)
+        ones = blk([np.ones(D)], T, H, Dh, dtype)
+        z = np.zeros(1, dtype=np.int32)
+        s = oracle.score_pairs(dtype, oracle.BLOCK, kq, ones, kp, ones, z, z, z)[0]
+        nx, _ = oracle.block_norms(dtype, oracle.BLOCK, kq, ones)
+        ny, _ = oracle.block_norms(dtype, oracle.BLOCK, kp, ones)
+        nx, ny = nx[0, 0], ny[0, 0]
+        xy = (2 * s - 1) * np.sqrt(nx * ny)
+        direct = oracle.sqdist(dtype, x, y)
+        assert direct == pytest.approx(nx + ny - 2 * xy, rel=1e-12, abs=1e-12)
+        # and against numpy on library-decoded values
+        xd, yd = dec(x, dtype), dec(y, dtype)
+        assert direct == pytest.approx(((xd - yd) ** 2).sum(), rel=1e-13)
+        assert xy == pytest.approx(float(xd @ yd), rel=1e-11, abs=1e-11)
+        # unit vectors: |x^ - y^|^2 = 2 - 2 cos
+        cos = 2 * s - 1
+        assert ((xd / np.sqrt(nx) - yd / np.sqrt(ny)) ** 2).sum() == pytest.approx(2 - 2 * cos, abs=1e-12)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_duplicate_is_exactly_one_and_orthogonal_exactly_zero(oracle, mode):
+    rng = np.random.RandomState(3)
+    T, H, Dh = 16, 8, 128
+    D = T * H * Dh
+    x = rng.randn(2, D).astype(np.float32)
+    k, v = blk(x[:1], T, H, Dh, 0), blk(x[1:], T, H, Dh, 0)
+    z = np.zeros(1, dtype=np.int32)
+    assert oracle.score_pairs(0, mode, k, v, k.copy(), v.copy(), z, z, z)[0] == 1.0
+    # disjoint supports: even dims vs odd dims
+    a, b = x.copy(), x.copy()
+    a[:, 0::2] = 0
+    b[:, 1::2] = 0
+    s = oracle.score_pairs(0, mode, blk(a[:1], T, H, Dh, 0), blk(a[1:], T, H, Dh, 0),
+                           blk(b[:1], T, H, Dh, 0), blk(b[1:], T, H, Dh, 0), z, z, z)[0]
+    assert s == 0.0
+    # all-zero query: defined as 0, never NaN, never a match for tau > 0
+    zero = np.zeros((1, 1, T, H, Dh), dtype=np.uint16)
+    r = oracle.match(0, mode, zero, zero, k, v, None, 0.5)
+    assert r["best_score"][0, 0] == 0.0 and r["match_idx"][0, 0] == -1
+
+
+def test_noisy_copy_law_and_fresh_pairs(oracle):
+    # x ~ N(0,1)^D, y = x + N(0, sigma^2): cos -> 1/sqrt(1 + sigma^2); independent pairs: cos ~ N(0, 1/D).
+    rng = np.random.RandomState(9)
+    T, H, Dh = 16, 8, 128
+    D = T * H * Dh
+    pool = rng.randn(4, 2, D).astype(np.float32)
+    for sigma in (0.1, 0.15):
+        q = pool + sigma * rng.randn(4, 2, D).astype(np.float32)
+        for i in range(4):
+            z = np.zeros(1, dtype=np.int32)
+            s = oracle.score_pairs(0, 0, blk(q[i, :1], T, H, Dh, 0), blk(q[i, 1:], T, H, Dh, 0),
+                                   blk(pool[i, :1], T, H, Dh, 0), blk(pool[i, 1:], T, H, Dh, 0), z, z, z)[0]
+            assert s == pytest.approx(1 / np.sqrt(1 + sigma ** 2), abs=3e-3)
+    z = np.zeros(1, dtype=np.int32)
+    s = oracle.score_pairs(0, 0, blk(pool[0, :1], T, H, Dh, 0), blk(pool[0, 1:], T, H, Dh, 0),
+                           blk(pool[1, :1], T, H, Dh, 0), blk(pool[1, 1:], T, H, Dh, 0), z, z, z)[0]
+    assert abs(s) < 6 / np.sqrt(D)
+
+
+def test_per_head_rule_adversarial(oracle):
+    # Seven heads exact copies, one head with sigma = 0.5 noise: the whole-block cosine stays
+    # near 8/sqrt(8 * 8.25) = 0.985 (would match at 0.95), the noisy head alone is near
+    # 1/sqrt(1.25) = 0.894, so "all heads must clear tau" must refuse the pair.
+    rng = np.random.RandomState(21)
+    T, H, Dh = 16, 8, 128
+    p = rng.randn(2, T, H, Dh).astype(np.float32)
+    q = p.copy()
+    q[:, :, 3, :] += 0.5 * rng.randn(2, T, Dh).astype(np.float32)
+    a = [blk(t.reshape(1, -1), T, H, Dh, 0) for t in (q[0], q[1], p[0], p[1])]
+    rb = oracle.match(0, 0, *a, None, 0.95)
+    rh = oracle.match(0, 1, *a, None, 0.95)
+    assert rb["best_score"][0, 0] == pytest.approx(8 / np.sqrt(8 * 8.25), abs=4e-3) and rb["match_idx"][0, 0] == 0
+    assert rh["best_score"][0, 0] == pytest.approx(1 / np.sqrt(1.25), abs=1e-2) and rh["match_idx"][0, 0] == -1
+
+
+# ---------------------------------------------------------------- search
+def brute_scores(kq, vq, kp, vp, dtype, mode):
+    """Score matrix by a different route: cos = 1 - |x^ - y^|^2 / 2 on library-decoded values."""
+    L, Q, T, H, Dh = kq.shape
+    P = kp.shape[1]
+    d = [dec(a, dtype).reshape(a.shape) for a in (kq, vq, kp, vp)]
+    out = np.zeros((L, Q, P))
+
+    def cos(x, y):
+        nx, ny = np.sqrt((x * x).sum()), np.sqrt((y * y).sum())
+        if nx == 0 or ny == 0:
+            return 0.0
+        return 1.0 - (((x / nx) - (y / ny)) ** 2).sum() / 2.0
+
+    for l in range(L):
+        for q in range(Q):
+            for p in range(P):
+                if mode == 0:
+                    out[l, q, p] = 0.5 * (cos(d[0][l, q], d[2][l, p]) + cos(d[1][l, q], d[3][l, p]))
+                else:
+                    out[l, q, p] = min(0.5 * (cos(d[0][l, q, :, h], d[2][l, p, :, h]) +
+                                              cos(d[1][l, q, :, h], d[3][l, p, :, h])) for h in range(H))
+    return out
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_match_vs_brute_force(oracle, dtype, mode):
+    rng = np.random.RandomState(100 + 10 * dtype + mode)
+    L, Q, P, T, H, Dh = 2, 5, 9, 2, 3, 4
+    D = T * H * Dh
+    kp, vp = rng.randn(L, P, D), rng.randn(L, P, D)
+    kq, vq = rng.randn(L, Q, D), rng.randn(L, Q, D)
+    kq[:, 0], vq[:, 0] = kp[:, 4] + 0.05 * rng.randn(L, D), vp[:, 4] + 0.05 * rng.randn(L, D)
+    kq[:, 1], vq[:, 1] = kp[:, 7], vp[:, 7]
+    a = [enc(t, dtype).reshape(L, -1, T, H, Dh) for t in (kq, vq, kp, vp)]
+    live = np.ones((L, P), dtype=np.uint8)
+    live[0, 7] = 0          # the exact copy's partner is dead in layer 0 only
+    live[1, 2] = 0
+    tau = 0.9
+    r = oracle.match(dtype, mode, *a, live, tau, want_scores=True)
+    S = brute_scores(*a, dtype, mode)
+    assert np.allclose(r["scores"], S, atol=1e-12, rtol=0)
+    Sl = np.where(live[:, None, :] == 1, S, -np.inf)
+    assert np.array_equal(r["best_idx"], Sl.argmax(axis=2))
+    assert np.allclose(r["best_score"], Sl.max(axis=2), atol=1e-12)
+    assert np.allclose(r["second_score"], np.sort(Sl, axis=2)[:, :, -2], atol=1e-12)
+    want_match = np.where(Sl.max(axis=2) >= tau, Sl.argmax(axis=2), -1)
+    # keep the comparison away from rounding at the threshold
+    assert (np.abs(Sl.max(axis=2) - tau) > 1e-9).all()
+    assert np.array_equal(r["match_idx"], want_match)
+    assert r["match_idx"][1, 1] == 7 and r["best_score"][1, 1] == 1.0
+    assert r["best_idx"][0, 1] != 7        # dead blocks are skipped, not merely rejected
+
+
+def test_tie_break_threshold_and_empty_pool(oracle):
+    rng = np.random.RandomState(2)
+    T, H, Dh = 2, 2, 4
+    D = T * H * Dh
+    pool = rng.randn(6, D)
+    pool[4] = pool[1]                      # bit-identical pool blocks at 1 and 4
+    q = pool[[4]]
+    a = [blk(t, T, H, Dh, 0) for t in (q, q, pool, pool)]
+    r = oracle.match(0, 0, *a, None, 1.0)
+    assert r["best_idx"][0, 0] == 1 and r["match_idx"][0, 0] == 1        # lowest index; >= tau at tau = 1
+    assert r["best_score"][0, 0] == 1.0 and r["second_score"][0, 0] == 1.0   # runner-up counted with multiplicity
+    live = np.ones((1, 6), dtype=np.uint8)
+    live[0, 1] = 0
+    r = oracle.match(0, 0, *a, live, 1.0)
+    assert r["best_idx"][0, 0] == 4
+    r = oracle.match(0, 0, *a, np.zeros((1, 6), dtype=np.uint8), 0.5)
+    assert r["best_idx"][0, 0] == -1 and r["match_idx"][0, 0] == -1 and r["best_score"][0, 0] == -np.inf
+    r = oracle.match(0, 0, *a, None, np.nextafter(1.0, 2.0))
+    assert r["match_idx"][0, 0] == -1 and r["best_idx"][0, 0] == 1
+
+
+def test_cfg1_expected_matches(oracle):
+    # Tiny workload: the 8 planted queries (sigma 0.1 -> score ~0.995) match their targets, the 24 fresh
+    # ones (|score| ~ 1/sqrt(D)) match nothing.
+    w = synth.WORKLOADS[1]
+    pr = synth.make_problem(w, "cpu")
+    plan = pr["plan"]
+    r = oracle.match(0, w.mode, *(synth.bits(pr[n]) for n in ("kq", "vq", "kp", "vp")), pr["live"].numpy(), w.tau)
+    want = np.full(w.Q, -1)
+    want[plan.planted_slots] = plan.planted_targets
+    assert np.array_equal(r["match_idx"][0], want)
+    assert np.allclose(r["best_score"][0, plan.planted_slots], 1 / np.sqrt(1.01), atol=3e-3)
+    fresh = np.setdiff1d(np.arange(w.Q), plan.planted_slots)
+    assert (np.abs(r["best_score"][0, fresh]) < 0.06).all()
+
+
+# ---------------------------------------------------------------- remap
+def test_remap_golden(oracle):
+    cases = json.load(open(os.path.join(GOLD, "remap_handworked.json")))["cases"]
+    for c in cases:
+        r = oracle.remap(np.array([c["tables"]], dtype=np.int32), c["query_ids"], c["pool_ids"],
+                         np.array([c["match_idx"]], dtype=np.int32), c["P"], c["NB"],
+                         np.array([c["refcount"]], dtype=np.int32))
+        assert r["tables"][0].tolist() == c["tables_out"], c["name"]
+        assert r["refcount"][0].tolist() == c["refcount_out"], c["name"]
+        assert r["freed"][0].tolist() == c["freed"], c["name"]
+        assert int(r["n_remapped"][0]) == c["n_remapped"], c["name"]
+
+
+def random_remap_case(rng, L=3, P=40, Q=12, R=5, E=30):
+    NB = P + Q + 4
+    ids = rng.permutation(NB)
+    pool_ids, query_ids = ids[:P].astype(np.int32), ids[P:P + Q].astype(np.int32)
+    tables = rng.choice(np.concatenate([ids[:P + Q], [-1]]), size=(L, R, E)).astype(np.int32)
+    refcount = np.stack([np.bincount(t[t >= 0], minlength=NB) for t in tables]).astype(np.int32)
+    match = rng.randint(-1, P, size=(L, Q)).astype(np.int32)
+    match[rng.rand(L, Q) < 0.4] = -1
+    match[:, 1] = match[:, 0]              # two queries share a target
+    return tables, query_ids, pool_ids, match, P, NB, refcount
+
+
+def test_remap_invariants(oracle):
+    rng = np.random.RandomState(8)
+    for _ in range(10):
+        tables, qids, pids, match, P, NB, rc = random_remap_case(rng)
+        r = oracle.remap(tables, qids, pids, match, P, NB, rc)
+        # references are conserved and refcounts stay equal to the number of table references
+        assert np.array_equal(r["refcount"].sum(axis=1), rc.sum(axis=1))
+        for l in range(tables.shape[0]):
+            t = r["tables"][l]
+            assert np.array_equal(r["refcount"][l], np.bincount(t[t >= 0], minlength=NB))
+            matched = match[l] >= 0
+            # every reference of a matched query block moved, so it is freed; unmatched ones are not
+            assert np.array_equal(r["freed"][l].astype(bool), matched)
+            assert not np.isin(t, qids[matched]).any()
+            untouched = ~np.isin(tables[l], qids[matched])
+            assert np.array_equal(t[untouched], tables[l][untouched])
+            assert r["n_remapped"][l] == (~untouched).sum()
+            # tables only point at blocks that are still referenced
+            assert (r["refcount"][l][t[t >= 0]] >= 1).all()
+        # idempotence: a second application changes nothing
+        r2 = oracle.remap(r["tables"], qids, pids, match, P, NB, r["refcount"])
+        assert np.array_equal(r2["tables"], r["tables"]) and np.array_equal(r2["refcount"], r["refcount"])
+        assert (r2["n_remapped"] == 0).all()
+
+
+def test_remap_no_match_is_identity(oracle):
+    rng = np.random.RandomState(4)
+    tables, qids, pids, match, P, NB, rc = random_remap_case(rng)
+    match[:] = -1
+    r = oracle.remap(tables, qids, pids, match, P, NB, rc)
+    assert np.array_equal(r["tables"], tables) and np.array_equal(r["refcount"], rc)
+    assert not r["freed"].any() and not r["n_remapped"].any()
