@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the reusable-KV-block search on one MI355X.
+
+A step is one pass of the whole hot path over one batch of new blocks, all layers:
+  rc_block_norms(query blocks) -> rc_match_blocks(queries x resident pool) -> rc_remap_block_table
+with the pool's squared norms cached from when the blocks were sealed (the paper's
+Stage 2 computes a block's norms once and reuses them).  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # dense MFMA, MI355X
+PEAK_HBM_GBS = 8000.0
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, pr, n_layers):
+    """The oracle as it stands, timed on the host cores on the first `n_layers` layers of the workload."""
+    from oracle import rc_oracle
+    from paper_2507_21433_amd import synth
+    rc_oracle.build()
+    a = [synth.bits(pr[n][:n_layers]) for n in ("kq", "vq", "kp", "vp")]
+    live = pr["live"][:n_layers].cpu().numpy()
+    t0 = time.time()
+    rc_oracle.match(0 if w.dtype == "f16" else 1, w.mode, *a, live, w.tau)
+    dt = time.time() - t0
+    pairs = n_layers * w.P * w.Q
+    return {"value": pairs / dt, "unit": "pairs/s", "cores": rc_oracle.n_threads(), "kind": "oracle",
+            "sample": f"rc_oracle.match on the first {n_layers} of {w.L} layers of {w.name} "
+                      f"({pairs} pairs, {dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=2, help="1..5, the workloads of the benchmark definition")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
+    ap.add_argument("--cpu-layers", type=int, default=2, help="layers the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_21433_amd import binding as rc
+    from paper_2507_21433_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    rc.lib()   # fail loudly if the HIP library is not built
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    if args.layers:
+        w = synth.scaled(w, L=args.layers)
+    log(f"workload {w.name}: L={w.L} P={w.P} Q={w.Q} T={w.T} dtype={w.dtype} mode={w.mode}")
+    t0 = time.time()
+    pr = synth.make_problem(w, dev)
+    torch.cuda.synchronize()
+    log(f"inputs resident ({(w.L * (w.P + w.Q) * w.block_bytes) / 1e9:.1f} GB of KV) after {time.time() - t0:.1f} s")
+
+    L, P, Q = w.L, w.P, w.Q
+    # pool norms: computed when the blocks were sealed, cached since (also timed once, as the cold fill)
+    pk, pv = rc.rc_block_norms(pr["kp"], pr["vp"], w.mode)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    rc.rc_block_norms(pr["kp"], pr["vp"], w.mode, pk, pv)
+    e1.record()
+    torch.cuda.synchronize()
+    pool_norm_ms = e0.elapsed_time(e1)
+
+    nshape = (L, Q) if w.mode == 0 else (L, Q, w.H)
+    qk = torch.empty(nshape, dtype=torch.float32, device=dev)
+    qv = torch.empty(nshape, dtype=torch.float32, device=dev)
+    ws_match = torch.empty(rc.rc_match_workspace_size(pr["kq"], w.mode, Q, P), dtype=torch.uint8, device=dev)
+    ws_remap = torch.empty(rc.rc_remap_workspace_size(L, w.R, w.E, Q, w.NB), dtype=torch.uint8, device=dev)
+    out = dict(best_idx=torch.empty((L, Q), dtype=torch.int32, device=dev),
+               best_score=torch.empty((L, Q), dtype=torch.float32, device=dev),
+               match_idx=torch.empty((L, Q), dtype=torch.int32, device=dev),
+               second_score=torch.empty((L, Q), dtype=torch.float32, device=dev))
+
+    remap_out = dict(tables=torch.empty_like(pr["tables"]), refcount=torch.empty_like(pr["refcount"]),
+                     freed=torch.empty((L, Q), dtype=torch.uint8, device=dev),
+                     n_remapped=torch.empty((L,), dtype=torch.int32, device=dev))
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        rc.rc_block_norms(pr["kq"], pr["vq"], w.mode, qk, qv)
+        if ev:
+            ev[1].record()
+        rc.rc_match_blocks(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, pr["live"], w.tau, w.mode,
+                           workspace=ws_match, out=out)
+        if ev:
+            ev[2].record()
+        res = rc.rc_remap_block_table(pr["tables"], pr["query_ids"], None, out["match_idx"], P, w.NB, pr["refcount"],
+                                      workspace=ws_remap, out=remap_out)
+        if ev:
+            ev[3].record()
+        return res
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        res = step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    norm_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    match_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    remap_ms = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+
+    pairs = L * P * Q
+    flop = pairs * 4.0 * w.D                       # 2 (mul+add) x D x 2 (K and V) per pair
+    kv_bytes = L * (P + Q) * w.block_bytes         # every pool and query block read once
+    match_tflops = flop / (match_ms * 1e-3) / 1e12
+    roofline = {"kernel": "match_tile_kernel (inside rc_match_blocks)", "bound": "mfma",
+                "achieved": match_tflops, "peak": PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
+                "frac": match_tflops / PEAK_TFLOPS[w.dtype], "traffic": None}
+    match_gbs = kv_bytes / (match_ms * 1e-3) / 1e9
+    qnorm_bytes = L * Q * w.block_bytes
+    remap_bytes = L * (2 * w.R * w.E * 4 + 2 * w.NB * 4)
+    kernels = {
+        "rc_match_blocks": {"ms": match_ms, "tflops": match_tflops, "kv_gb_per_s": match_gbs,
+                            "hbm_frac": match_gbs / PEAK_HBM_GBS,
+                            "flop_per_byte": flop / kv_bytes},
+        "rc_block_norms(queries)": {"ms": norm_ms, "gb_per_s": qnorm_bytes / (norm_ms * 1e-3) / 1e9},
+        "rc_block_norms(pool, cold fill, not in the step)": {
+            "ms": pool_norm_ms, "gb_per_s": L * P * w.block_bytes / (pool_norm_ms * 1e-3) / 1e9,
+            "hbm_frac": L * P * w.block_bytes / (pool_norm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "rc_remap_block_table": {"ms": remap_ms, "gb_per_s": remap_bytes / (remap_ms * 1e-3) / 1e9},
+    }
+    matched = int((out["match_idx"] >= 0).sum().item())
+    n_remapped = int(res["n_remapped"].sum().item())
+
+    cpu = None
+    if args.cpu_layers > 0:
+        log("timing the CPU oracle on the host cores ...")
+        cpu = cpu_baseline(w, pr, min(args.cpu_layers, L))
+
+    line = {
+        "metric": "block_pair_scores_per_s", "value": pairs / (ms_step * 1e-3), "unit": "pairs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers": L, "pool_blocks_per_layer": P, "query_blocks_per_layer": Q,
+                   "block_tokens": w.T, "kv_heads": w.H, "head_dim": w.Dh, "mode": "block" if w.mode == 0 else "per_head_all",
+                   "tau": w.tau, "tables": [w.R, w.E], "pool_norms": "cached"},
+        "kv_gb_per_s": kv_bytes / (ms_step * 1e-3) / 1e9,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+        "matched_queries": matched, "remapped_entries": n_remapped,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,253 @@
+// rc_remap_block_table: zero-copy sharing applied to the PagedAttention block tables
+// (ReasonCache Sec. IV-B: the kept block's reference count goes up, the table entry is
+// rewritten, nothing is copied; a block is freed only at reference count 0).
+//
+// Four stream-ordered launches, no atomics anywhere:
+//   1. prepare : slot_of[b] = -1 for every physical block, refcount_out = refcount_in
+//   2. scatter : slot_of[query_ids[q]] = q
+//   3. gather  : table_out[e] = target of table_in[e]; references to matched query blocks are
+//                counted per workgroup in an LDS histogram that one wave at a time updates
+//                (equal keys inside a wave are merged with ballots), then stored as partials
+//   4. finalize: per layer, cnt[q] = sum of partials; the query block loses cnt references,
+//                its target gains them.  Queries that share a target take turns through a
+//                small claim table in LDS, one winner per slot and round.
+#include <hip/hip_runtime.h>
+
+#include "rc_common.hpp"
+
+namespace rc {
+namespace {
+
+constexpr int kGatherThreads = 256;
+constexpr int kGatherPerThread = 16;                                  // entries a thread keeps in flight
+constexpr int kGatherBatch = kGatherThreads * kGatherPerThread;       // entries per batch of a workgroup
+constexpr int kMaxQ = 8192;                                           // LDS histogram bins
+constexpr int kFinalThreads = 1024;
+constexpr int kFinalPerThread = kMaxQ / kFinalThreads;
+constexpr int kClaimSlots = 4096;
+
+// How the R*E entries of a layer are cut into workgroups: large enough chunks that the
+// per-workgroup partial histogram (Q ints) stays a small fraction of the table traffic.
+inline int64_t chunks_per_layer(int64_t RE, int64_t Q) {
+  const int64_t min_chunk = (4 * Q > kGatherBatch) ? 4 * Q : kGatherBatch;
+  int64_t g = RE / min_chunk;
+  if (g < 1) g = 1;
+  if (g > 65535) g = 65535;
+  return g;
+}
+
+__global__ __launch_bounds__(256) void remap_prepare_kernel(int32_t* __restrict__ slot_of, long long NB,
+                                                            const int32_t* refcount_in, int32_t* refcount_out,
+                                                            long long LNB) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < NB) slot_of[i] = -1;
+  if (i < LNB && refcount_in != refcount_out) refcount_out[i] = refcount_in[i];
+}
+
+__global__ __launch_bounds__(256) void remap_scatter_kernel(int32_t* __restrict__ slot_of,
+                                                            const int32_t* __restrict__ query_ids, int Q, long long NB) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q < Q) {
+    const int b = query_ids[q];
+    if (b >= 0 && b < NB) slot_of[b] = q;
+  }
+}
+
+// grid = (G, L).  Workgroup g rewrites entries [g*chunk, min((g+1)*chunk, RE)) of layer l.
+__global__ __launch_bounds__(kGatherThreads) void remap_gather_kernel(
+    const int32_t* tables_in, int32_t* tables_out, long long RE, long long chunk,
+    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ pool_ids,
+    const int32_t* __restrict__ match_idx, int Q, int P, long long NB, int32_t* __restrict__ partial) {
+  __shared__ int hist[kMaxQ];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long long l = blockIdx.y, g = blockIdx.x, G = gridDim.x;
+  for (int q = tid; q < Q; q += kGatherThreads) hist[q] = 0;
+  __syncthreads();
+  const int32_t* tin = tables_in + l * RE;
+  int32_t* tout = tables_out + l * RE;
+  const int32_t* m = match_idx + l * Q;
+  const long long lo = g * chunk, hi = (lo + chunk < RE) ? lo + chunk : RE;
+
+  for (long long base = lo; base < hi; base += kGatherBatch) {
+    int entry[kGatherPerThread], slot[kGatherPerThread];
+#pragma unroll
+    for (int k = 0; k < kGatherPerThread; ++k) {
+      const long long e = base + k * kGatherThreads + tid;
+      entry[k] = (e < hi) ? tin[e] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < kGatherPerThread; ++k) {
+      const int t = entry[k];
+      slot[k] = (t >= 0 && t < NB) ? slot_of[t] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < kGatherPerThread; ++k) {
+      int out = entry[k];
+      if (slot[k] >= 0) {
+        const int mi = m[slot[k]];
+        if (mi >= 0 && mi < P)
+          out = pool_ids ? pool_ids[mi] : mi;
+        else
+          slot[k] = -1;  // unmatched query block: entry stays, nothing to count
+      }
+      const long long e = base + k * kGatherThreads + tid;
+      if (e < hi) tout[e] = out;
+    }
+    // count the rewritten references, one wave at a time
+    bool any = false;
+#pragma unroll
+    for (int k = 0; k < kGatherPerThread; ++k) any |= slot[k] >= 0;
+    if (__syncthreads_or(any)) {
+      for (int w = 0; w < kGatherThreads / 64; ++w) {
+        if (wave == w) {
+#pragma unroll
+          for (int k = 0; k < kGatherPerThread; ++k) {
+            const int s = slot[k];
+            unsigned long long active = __ballot(s >= 0);
+            while (active) {
+              const int leader = __ffsll((long long)active) - 1;
+              const int key = __shfl(s, leader);
+              const unsigned long long same = __ballot(s == key);
+              if (lane == leader) hist[key] += __popcll(same);
+              active &= ~same;
+            }
+          }
+        }
+        __syncthreads();
+      }
+    }
+  }
+  __syncthreads();
+  int32_t* out = partial + (l * G + g) * Q;
+  for (int q = tid; q < Q; q += kGatherThreads) out[q] = hist[q];
+}
+
+// grid = L, one workgroup per layer.
+__global__ __launch_bounds__(kFinalThreads) void remap_finalize_kernel(
+    const int32_t* __restrict__ partial, int G, const int32_t* __restrict__ query_ids,
+    const int32_t* __restrict__ pool_ids, const int32_t* __restrict__ match_idx, int Q, int P, long long NB,
+    int32_t* refcount_out, uint8_t* __restrict__ freed, int32_t* __restrict__ n_remapped) {
+  __shared__ int claim[kClaimSlots];
+  __shared__ int wsum[kFinalThreads / 64];
+  const int tid = threadIdx.x;
+  const long long l = blockIdx.x;
+  const int32_t* m = match_idx + l * Q;
+  int32_t* rc_l = refcount_out + l * NB;
+
+  int cnt[kFinalPerThread], tgt[kFinalPerThread];
+  int moved = 0;
+#pragma unroll
+  for (int k = 0; k < kFinalPerThread; ++k) {
+    const int q = k * kFinalThreads + tid;
+    cnt[k] = 0;
+    tgt[k] = -1;
+    if (q < Q) {
+      const int mi = m[q];
+      const int b = query_ids[q];
+      unsigned char fr = 0;
+      if (mi >= 0 && mi < P && b >= 0 && b < NB) {
+        int c = 0;
+        for (int g = 0; g < G; ++g) c += partial[(l * G + g) * Q + q];
+        const int t = pool_ids ? pool_ids[mi] : mi;
+        const int left = rc_l[b] - c;
+        rc_l[b] = left;  // query ids are distinct: no other thread touches this entry
+        fr = (left == 0);
+        moved += c;
+        if (c > 0 && t >= 0 && t < NB) {
+          cnt[k] = c;
+          tgt[k] = t;
+        }
+      }
+      freed[l * Q + q] = fr;
+    }
+  }
+  // queries that share a target add their references in turns
+  bool pending = false;
+#pragma unroll
+  for (int k = 0; k < kFinalPerThread; ++k) pending |= tgt[k] >= 0;
+  while (__syncthreads_or(pending)) {
+#pragma unroll
+    for (int k = 0; k < kFinalPerThread; ++k)
+      if (tgt[k] >= 0) claim[tgt[k] & (kClaimSlots - 1)] = k * kFinalThreads + tid;
+    __syncthreads();
+    pending = false;
+#pragma unroll
+    for (int k = 0; k < kFinalPerThread; ++k)
+      if (tgt[k] >= 0) {
+        if (claim[tgt[k] & (kClaimSlots - 1)] == k * kFinalThreads + tid) {
+          rc_l[tgt[k]] += cnt[k];
+          tgt[k] = -1;
+        } else {
+          pending = true;
+        }
+      }
+    __threadfence_block();
+  }
+  // n_remapped = total references moved in this layer
+  for (int off = 32; off > 0; off >>= 1) moved += __shfl_xor(moved, off);
+  if ((tid & 63) == 0) wsum[tid >> 6] = moved;
+  __syncthreads();
+  if (tid == 0) {
+    int s = 0;
+    for (int w = 0; w < kFinalThreads / 64; ++w) s += wsum[w];
+    n_remapped[l] = s;
+  }
+}
+
+}  // namespace
+}  // namespace rc
+
+extern "C" size_t rc_remap_workspace_size(int32_t n_layers, int64_t R, int64_t E, int64_t Q, int64_t NB) {
+  using namespace rc;
+  if (n_layers < 0 || R < 0 || E < 0 || Q < 0 || NB < 0) return 0;
+  const int64_t G = chunks_per_layer(R * E, Q);
+  const int64_t ints = ((NB + 3) / 4) * 4 + (int64_t)n_layers * G * Q;
+  return (size_t)(ints > 0 ? ints : 4) * sizeof(int32_t);
+}
+
+extern "C" rc_status rc_remap_block_table(int32_t n_layers, const int32_t* tables_in, int32_t* tables_out, int64_t R,
+                                          int64_t E, const int32_t* query_ids, const int32_t* pool_ids,
+                                          const int32_t* match_idx, int64_t Q, int64_t P, int64_t NB,
+                                          const int32_t* refcount_in, int32_t* refcount_out, uint8_t* freed,
+                                          int32_t* n_remapped, void* workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
+  using namespace rc;
+  clear_error();
+  if (n_layers < 0 || R < 0 || E < 0 || Q < 0 || P < 0 || NB < 0)
+    return fail(RC_ERR_INVALID_ARG, "rc_remap_block_table: negative size");
+  if (Q > kMaxQ) return fail(RC_ERR_UNSUPPORTED, "rc_remap_block_table: Q %lld above %d", (long long)Q, kMaxQ);
+  if (!pool_ids && P > NB) return fail(RC_ERR_INVALID_ARG, "rc_remap_block_table: identity pool ids need P <= NB");
+  if (n_layers == 0) return RC_OK;
+  const int64_t RE = R * E;
+  if (n_layers > 65535 || NB > 0x7fffffffLL || P > 0x7fffffffLL || RE > (1LL << 40))
+    return fail(RC_ERR_UNSUPPORTED, "rc_remap_block_table: problem beyond the grid limits");
+  if (!n_remapped || (RE > 0 && (!tables_in || !tables_out)) || (NB > 0 && (!refcount_in || !refcount_out)) ||
+      (Q > 0 && (!query_ids || !match_idx || !freed)))
+    return fail(RC_ERR_INVALID_ARG, "rc_remap_block_table: NULL pointer");
+  const size_t need = rc_remap_workspace_size(n_layers, R, E, Q, NB);
+  if (!workspace || workspace_bytes < need || !aligned16(workspace))
+    return fail(RC_ERR_WORKSPACE, "rc_remap_block_table: workspace of %zu bytes needed (16-byte aligned), got %zu",
+                need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int32_t* slot_of = static_cast<int32_t*>(workspace);
+  int32_t* partial = slot_of + ((NB + 3) / 4) * 4;
+  const int64_t G = chunks_per_layer(RE, Q);
+  const int64_t chunk = (RE + G - 1) / G;
+  const long long LNB = (long long)n_layers * NB;
+
+  if (LNB > 0) {
+    remap_prepare_kernel<<<(unsigned)((LNB + 255) / 256), 256, 0, st>>>(slot_of, NB, refcount_in, refcount_out, LNB);
+    if (rc_status s = check_launch("rc_remap_block_table(prepare)")) return s;
+  }
+  if (Q > 0 && NB > 0) {
+    remap_scatter_kernel<<<(unsigned)((Q + 255) / 256), 256, 0, st>>>(slot_of, query_ids, (int)Q, NB);
+    if (rc_status s = check_launch("rc_remap_block_table(scatter)")) return s;
+  }
+  remap_gather_kernel<<<dim3((unsigned)G, (unsigned)n_layers), kGatherThreads, 0, st>>>(
+      tables_in, tables_out, RE, chunk, slot_of, pool_ids, match_idx, (int)Q, (int)P, NB, partial);
+  if (rc_status s = check_launch("rc_remap_block_table(gather)")) return s;
+  remap_finalize_kernel<<<(unsigned)n_layers, kFinalThreads, 0, st>>>(partial, (int)G, query_ids, pool_ids, match_idx,
+                                                                      (int)Q, (int)P, NB, refcount_out, freed,
+                                                                      n_remapped);
+  return check_launch("rc_remap_block_table(finalize)");
+}

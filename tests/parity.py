@@ -1,0 +1,61 @@
+"""Comparison rule between the HIP path and the CPU oracle (test helper, no GPU code).
+
+Scores agree to 2e-3 absolute.  A query is *ambiguous* when the oracle's best score is
+within 2e-3 of the threshold or of the runner-up; only there may indices differ, and
+then the GPU's choice must still be within 2e-3 of the oracle's best.  Everything else
+is bit-exact.
+"""
+import numpy as np
+
+TOL = 2e-3
+
+
+def check_match(gpu, orc, tau, score_at_gpu_idx, tol=TOL):
+    """gpu / orc: dicts of numpy arrays [L][Q]; score_at_gpu_idx: oracle score of (q, gpu best_idx), NaN where idx < 0.
+
+    Returns a report dict; raises AssertionError with a description on a violation.
+    """
+    gi, gs, gm = gpu["best_idx"], gpu["best_score"].astype(np.float64), gpu["match_idx"]
+    oi, os_, om, o2 = orc["best_idx"], orc["best_score"], orc["match_idx"], orc["second_score"]
+    has = oi >= 0
+    assert np.array_equal(gi >= 0, has), "GPU and oracle disagree on whether any live pool block exists"
+    assert np.all(np.isneginf(gs[~has])) and np.all(gm[~has] == -1)
+
+    # 1. the score the GPU reports is the oracle's score of the block the GPU picked
+    err = np.abs(gs[has] - score_at_gpu_idx[has])
+    assert err.size == 0 or err.max() <= tol, f"best_score off by {err.max():.3e}"
+
+    near_tau = np.abs(os_ - tau) <= tol
+    near_tie = (os_ - o2) <= tol
+    amb = has & (near_tau | near_tie)
+    clear = has & ~amb
+    # 2. clear queries: bit-exact decisions
+    bad = clear & ((gi != oi) | (gm != om))
+    assert not bad.any(), f"{int(bad.sum())} non-ambiguous queries differ, first at {np.argwhere(bad)[0]}"
+    # 3. ambiguous queries: the GPU's pick is as good as the oracle's within tol, decision consistent
+    if amb.any():
+        assert (os_[amb] - score_at_gpu_idx[amb] <= tol).all(), "ambiguous pick is worse than the best by more than tol"
+        assert ((gm[amb] == -1) | (gm[amb] == gi[amb])).all()
+        decided = amb & ~near_tau
+        assert np.array_equal(gm[decided] >= 0, om[decided] >= 0), "threshold decision differs away from tau"
+    # 4. GPU-internal consistency of the decision with its own score
+    assert np.array_equal(gm >= 0, has & (gpu["best_score"] >= np.float32(tau)))
+    if gpu.get("second_score") is not None:
+        g2 = gpu["second_score"].astype(np.float64)
+        fin = np.isfinite(o2)
+        assert np.array_equal(np.isfinite(g2), fin)
+        assert fin.sum() == 0 or np.abs(g2[fin] - o2[fin]).max() <= tol, "runner-up score off"
+    return dict(n=int(has.sum()), ambiguous=int(amb.sum()), near_tau=int((has & near_tau).sum()),
+                near_tie=int((has & near_tie).sum()), max_score_err=float(err.max()) if err.size else 0.0,
+                matched=int((gm >= 0).sum()),
+                ambiguous_list=[tuple(int(x) for x in a) for a in np.argwhere(amb)[:16]])
+
+
+def score_lookup(scores, idx):
+    """Oracle score of (l, q, idx[l, q]) from a full [L][Q][P] matrix; NaN where idx < 0."""
+    L, Q, _ = scores.shape
+    out = np.full((L, Q), np.nan)
+    ok = idx >= 0
+    ll, qq = np.nonzero(ok)
+    out[ll, qq] = scores[ll, qq, idx[ll, qq]]
+    return out

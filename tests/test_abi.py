@@ -1,0 +1,106 @@
+"""The C-ABI library loads, exports what include/rc.h declares, and validates arguments on the host.
+
+No kernel is launched here: every call either has nothing to do or fails validation first.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_21433_amd import binding as rc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rc.LIB_PATH):
+        from paper_2507_21433_amd import build
+        build.build()
+    return rc.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rc_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(rc.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_error_string(lib):
+    assert lib.rc_version() >= 100
+    assert isinstance(lib.rc_last_error(), bytes)
+
+
+def desc(L=2, T=16, H=8, Dh=128, dtype=0, stride=None, n=4):
+    return rc.KvDesc(L, T, H, Dh, dtype, n * T * H * Dh if stride is None else stride)
+
+
+FAKE = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails before any launch
+ODD = ctypes.c_void_p(0x1004)
+
+
+def test_norms_validation(lib):
+    d = desc()
+    assert lib.rc_block_norms(ctypes.byref(d), 0, None, None, 0, None, None, None) == 0     # nothing to do
+    assert lib.rc_block_norms(None, 0, FAKE, FAKE, 4, FAKE, FAKE, None) == 1
+    assert lib.rc_block_norms(ctypes.byref(d), 0, None, FAKE, 4, FAKE, FAKE, None) == 1
+    assert b"NULL" in lib.rc_last_error()
+    assert lib.rc_block_norms(ctypes.byref(d), 0, ODD, FAKE, 4, FAKE, FAKE, None) == 1
+    assert lib.rc_block_norms(ctypes.byref(d), 0, FAKE, FAKE, -1, FAKE, FAKE, None) == 1
+    assert lib.rc_block_norms(ctypes.byref(d), 5, FAKE, FAKE, 4, FAKE, FAKE, None) == 2
+    for bad in (desc(Dh=64), desc(T=8), desc(H=17), desc(dtype=3)):
+        assert lib.rc_block_norms(ctypes.byref(bad), 0, FAKE, FAKE, 4, FAKE, FAKE, None) == 2
+    small = desc(stride=100)
+    assert lib.rc_block_norms(ctypes.byref(small), 0, FAKE, FAKE, 4, FAKE, FAKE, None) == 1
+    assert lib.rc_block_norms(ctypes.byref(d), 0, FAKE, FAKE, 4, FAKE, FAKE, None) != 99  # (valid call not made)
+
+
+def test_match_validation(lib):
+    q, p = desc(n=4), desc(n=64)
+    args = lambda **kw: [kw.get("qd", ctypes.byref(q)), kw.get("pd", ctypes.byref(p)), kw.get("mode", 0),
+                         kw.get("kq", FAKE), FAKE, kw.get("Q", 4), FAKE, FAKE, FAKE, FAKE, kw.get("P", 64), FAKE, FAKE,
+                         None, kw.get("tau", 0.9), FAKE, FAKE, FAKE, None, kw.get("ws", FAKE), kw.get("wsb", 1 << 20),
+                         None]
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 0, 4, 64) == 2 * 1 * 4 * 16
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 0, 4, 257) == 2 * 2 * 4 * 16
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 9, 4, 64) == 0
+    assert lib.rc_match_blocks(*args(Q=0)) == 0                      # nothing to do
+    assert lib.rc_match_blocks(*args(wsb=8)) == 3
+    assert b"workspace" in lib.rc_last_error()
+    assert lib.rc_match_blocks(*args(ws=None)) == 3
+    assert lib.rc_match_blocks(*args(kq=None)) == 1
+    assert lib.rc_match_blocks(*args(kq=ODD)) == 1
+    assert lib.rc_match_blocks(*args(tau=float("nan"))) == 1
+    assert lib.rc_match_blocks(*args(mode=2)) == 2
+    other = desc(n=64, T=32)
+    assert lib.rc_match_blocks(*args(pd=ctypes.byref(other))) == 1
+    assert lib.rc_match_blocks(*args(Q=-1)) == 1
+
+
+def test_remap_validation(lib):
+    args = lambda **kw: [kw.get("L", 2), FAKE, FAKE, kw.get("R", 4), kw.get("E", 8), FAKE, kw.get("pids", None), FAKE,
+                         kw.get("Q", 4), kw.get("P", 16), kw.get("NB", 20), kw.get("rin", FAKE), FAKE, FAKE, FAKE,
+                         kw.get("ws", FAKE), kw.get("wsb", 1 << 20), None]
+    need = lib.rc_remap_workspace_size(2, 4, 8, 4, 20)
+    assert need >= 20 * 4 + 2 * 4 * 4
+    assert lib.rc_remap_block_table(*args(L=0)) == 0
+    assert lib.rc_remap_block_table(*args(wsb=need - 1)) == 3
+    assert lib.rc_remap_block_table(*args(Q=8193)) == 2
+    assert lib.rc_remap_block_table(*args(P=21)) == 1                 # identity pool ids need P <= NB
+    assert lib.rc_remap_block_table(*args(rin=None)) == 1
+    assert lib.rc_remap_block_table(*args(R=-1)) == 1
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(rc, "_lib", None)
+    monkeypatch.setattr(rc, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        rc.lib()
