@@ -12,7 +12,7 @@ SOURCES = ["rc_norms.hip", "rc_match.hip", "rc_remap.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", "-Wno-unused-const-variable",
 ]
 
 

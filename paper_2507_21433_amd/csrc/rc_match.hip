@@ -7,10 +7,14 @@
 // rows of the MFMA tile (they land in the accumulator registers of a lane), query blocks are the
 // columns (they land on lanes), so the argmax over the pool is mostly an in-lane reduction.
 //
-// One workgroup owns a BP x BQ tile of S for the whole reduction (no split-K, so the selection
-// can be fused).  Operand slices of 64 elements (128 bytes per block) are copied global -> LDS
-// with direct-to-LDS 16-byte loads into a two-stage ring; the 16-byte chunks of a row are
-// XOR-swizzled by the row number so that the 32 rows a fragment read touches hit distinct banks.
+// One workgroup (4 waves, one per SIMD) owns a BP x BQ tile of S for the whole reduction (no
+// split-K, so the selection can be fused); each wave holds a (BP/2) x (BQ/2) accumulator tile.
+// Operand slices of 64 elements (128 bytes per block, one L2 line) go global -> LDS with
+// direct-to-LDS 16-byte buffer loads.  The workload is HBM-bound when few queries share a pool
+// block, and what bounds it then is the number of pool bytes in flight per compute unit, so all
+// of the 160 KB of LDS is ring buffer: three stages for the pool slices (two always in flight)
+// and two for the query slices, which come from the L2.  The 16-byte chunks of an LDS row are
+// XOR-swizzled by the row number so that fragment reads spread over all banks.
 //
 // K and V are normalised by different norms but share one accumulator tile: after the K
 // phase the accumulators are multiplied by (aKq aKp)/(aVq aVp), the V phase continues into
@@ -26,13 +30,12 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-#define RC_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
-#define RC_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;             // reduction elements per pipeline step
-constexpr int kRowBytes = kBK * 2;  // bytes of one block's slice in LDS
-constexpr int kSrdFlags = 0x00020000;  // raw 32-bit buffer descriptor word 3
+constexpr int kRowBytes = kBK * 2;  // bytes of one block's slice in LDS (one 128-byte line)
+constexpr int kThreads = 256;       // 4 waves as 2 (pool) x 2 (query)
+constexpr int kPoolStages = 3, kQueryStages = 2;
 
 // Partial selection result of one pool tile for one query.
 struct Part {
@@ -46,7 +49,7 @@ struct MatchParams {
   const char *kq, *vq, *kp, *vp;
   const float *q_ksq, *q_vsq, *p_ksq, *p_vsq;
   const uint8_t* live;
-  Part* part;                      // [L][npt][Q]
+  Part* part;                          // [L][npt][Q]
   long long q_lstride_b, p_lstride_b;  // bytes between layers
   int L, Q, P;
   int T, H;
@@ -80,31 +83,74 @@ __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-__device__ __forceinline__ float inv_sqrt_or(float sq, float if_zero) { return sq > 0.f ? 1.0f / sqrtf(sq) : if_zero; }
+// From the squared norms of a block's K and V tensors: ratio = aK/aV and av = aV with
+// a = 1/sqrt(squared norm).  A zero K norm gives aK = 0 (cosine defined as 0); a zero V norm
+// gives aV = 1, which is harmless because every V dot product of that block is 0 as well.
+// v_rsq_f32 is good to 1 ulp; the scores only need 2e-3.
+__device__ __forceinline__ void norm_factors(float ksq, float vsq, float& ratio, float& av) {
+  const float ak = ksq > 0.f ? __builtin_amdgcn_rsqf(ksq) : 0.f;
+  av = vsq > 0.f ? __builtin_amdgcn_rsqf(vsq) : 1.f;
+  const float inv_av = vsq > 0.f ? vsq * av : 1.f;  // sqrt(vsq)
+  ratio = ak * inv_av;
+}
+
+// Raw buffer descriptor (base, no stride, byte range, 32-bit raw data format) in scalar registers.
+__device__ __forceinline__ i32x4 make_srd(const void* base, uint32_t bytes) {
+  const unsigned long long a = (unsigned long long)base;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+  r[1] = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
+}
+
+// 16 bytes per lane, global -> LDS without passing through registers: lane l lands at LDS byte
+// lds_base + 16*l.  Completion is counted by vmcnt, in issue order.  Written as asm so that the
+// pipeline's waits are exactly the ones placed by hand below.
+__device__ __forceinline__ void dma16(i32x4 srd, uint32_t voff, uint32_t soff, uint32_t lds_base) {
+  // the descriptor, the scalar offset and the LDS base are the same for the whole wave
+  srd[0] = __builtin_amdgcn_readfirstlane(srd[0]);
+  srd[1] = __builtin_amdgcn_readfirstlane(srd[1]);
+  srd[2] = __builtin_amdgcn_readfirstlane(srd[2]);
+  srd[3] = __builtin_amdgcn_readfirstlane(srd[3]);
+  soff = __builtin_amdgcn_readfirstlane(soff);
+  lds_base = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
+               :
+               : "v"(voff), "s"(srd), "s"(soff), "s"(lds_base)
+               : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+// Position in the reduction: phase ph (tensor = ph & 1, head = ph >> 1), step u of the phase.
+struct Cursor {
+  int u, ph;
+};
 
 }  // namespace
 
-// BP x BQ tile, WP x WQ waves, each wave (BP/WP) x (BQ/WQ).  MODE 0 = block score, 1 = per-head-all.
-template <bool BF16, int BP, int BQ, int WP, int WQ, int MODE, int MINBLK>
-__global__ __launch_bounds__(64 * WP * WQ, MINBLK) void match_tile_kernel(const MatchParams p) {
-#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (buffer-resource types are device-only)
-  constexpr int NT = 64 * WP * WQ;
+// BP x BQ tile of one layer.  MODE 0 = block score, 1 = per-head-all.
+template <bool BF16, int BP, int BQ, int MODE>
+__global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
+  constexpr int NT = kThreads, WP = 2, WQ = 2;
   constexpr int WTP = BP / WP, WTQ = BQ / WQ;
   constexpr int TP = WTP / 32, TQ = WTQ / 32;
   constexpr int LA = BP * 8 / NT, LB = BQ * 8 / NT;  // 16-byte loads per thread per step
+  constexpr int SA = kPoolStages, SB = kQueryStages;
+  constexpr int A_STAGE = BP * kRowBytes, B_STAGE = BQ * kRowBytes;
+  constexpr int RING = SA * A_STAGE + SB * B_STAGE;
   static_assert(BP % (32 * WP) == 0 && BQ % (32 * WQ) == 0, "wave tiles are multiples of 32");
-  static_assert((BP * 8) % NT == 0 && (BQ * 8) % NT == 0, "loads divide evenly");
   static_assert(NT >= BQ, "one thread per query column in the tile epilogue");
+  static_assert(RING <= 160 * 1024, "ring fits the LDS of a compute unit");
+  static_assert(sizeof(Part) * WP * BQ <= RING, "the epilogue scratch reuses the ring");
 
-  // Separate arrays per stage so that reads of one stage are known not to alias the
-  // direct-to-LDS writes into the other.
-  __shared__ __attribute__((aligned(1024))) char sA0[BP * kRowBytes];
-  __shared__ __attribute__((aligned(1024))) char sB0[BQ * kRowBytes];
-  __shared__ __attribute__((aligned(1024))) char sA1[BP * kRowBytes];
-  __shared__ __attribute__((aligned(1024))) char sB1[BQ * kRowBytes];
-  __shared__ float s_rp[BP], s_fp[BP], s_bias[BP];  // pool rows: K/V ratio, final scale, -inf for dead/tail
-  __shared__ float s_rq[BQ], s_fq[BQ];              // query columns
-  __shared__ Part s_part[WP][BQ];
+  __shared__ __attribute__((aligned(1024))) char s_ring[RING];
+  const uint32_t ringA = lds_offset(s_ring), ringB = ringA + SA * A_STAGE;
 
   // ---- which tile: consecutive runs of `chunk` tiles go to one XCD (workgroups are dealt
   // round-robin to the 8 XCDs), so tiles that share operands share an L2.
@@ -125,46 +171,71 @@ __global__ __launch_bounds__(64 * WP * WQ, MINBLK) void match_tile_kernel(const 
   const long long row_b = (long long)D * 2;
   const int rowsA = min(BP, p.P - p0), rowsB = min(BQ, p.Q - q0);
 
-  // ---- buffer resources over this tile's rows of the four tensors (index 0 = K, 1 = V).  The
-  // range check of the buffer unit is a second guard; offsets are kept inside the rows anyway.
+  // ---- buffer descriptors over this tile's rows of the four tensors.  The range check of the
+  // buffer unit is a second guard; offsets are kept inside the rows anyway.
   const long long offPool = l * p.p_lstride_b + (long long)p0 * row_b;
   const long long offQry = l * p.q_lstride_b + (long long)q0 * row_b;
-  __amdgpu_buffer_rsrc_t resA[2], resB[2];
-  resA[0] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.kp + offPool), 0, (int)(rowsA * row_b), kSrdFlags);
-  resA[1] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.vp + offPool), 0, (int)(rowsA * row_b), kSrdFlags);
-  resB[0] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.kq + offQry), 0, (int)(rowsB * row_b), kSrdFlags);
-  resB[1] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.vq + offQry), 0, (int)(rowsB * row_b), kSrdFlags);
+  const i32x4 srdAk = make_srd(p.kp + offPool, (uint32_t)(rowsA * row_b));
+  const i32x4 srdAv = make_srd(p.vp + offPool, (uint32_t)(rowsA * row_b));
+  const i32x4 srdBk = make_srd(p.kq + offQry, (uint32_t)(rowsB * row_b));
+  const i32x4 srdBv = make_srd(p.vq + offQry, (uint32_t)(rowsB * row_b));
 
-  // ---- per-thread source offsets of the direct-to-LDS loads.  Load i of a wave fills LDS rows
-  // (i*NT + wave*64)/8 .. +7, lane -> (row lane/8, physical chunk lane%8); the logical chunk
-  // fetched is physical ^ (row & 7).  Rows past the end of the pool / queries re-read the last
-  // valid row (their results are masked), so no load leaves the tensors.
-  const uint32_t swz = (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
-  uint32_t offA[LA], offB[LB];
-#pragma unroll
-  for (int i = 0; i < LA; ++i) offA[i] = (uint32_t)min((i * NT + tid) >> 3, rowsA - 1) * (uint32_t)row_b + swz;
-#pragma unroll
-  for (int i = 0; i < LB; ++i) offB[i] = (uint32_t)min((i * NT + tid) >> 3, rowsB - 1) * (uint32_t)row_b + swz;
+  // ---- LDS layout of a stage: row r (one block) holds its 128-byte slice as eight 16-byte
+  // chunks; logical chunk c sits at physical chunk c ^ (r & 7).  A fragment read (32 consecutive
+  // rows, chunks 2kk and 2kk+1) then runs at the full LDS rate (measured: 110 B/clk per compute
+  // unit, against 32 B/clk for the unswizzled layout).
+  // Load i of a wave fills rows (i*NT + wave*64)/8 .. +7; lane -> (row lane/8, physical chunk
+  // lane%8).  The lane's byte offset for load 0 is a register, the row step of load i (32 rows)
+  // goes into the scalar offset.  Rows past the end of the pool / queries fall outside the
+  // descriptor's range and read as zeros (their results are masked anyway).
+  const int rho = lane >> 3;
+  const uint32_t src_chunk = (uint32_t)(((lane & 7) ^ rho) * 16);
+  const uint32_t voff = (uint32_t)(tid >> 3) * (uint32_t)row_b + src_chunk;
+  const uint32_t load_stride = (uint32_t)(NT / 8) * (uint32_t)row_b;
 
-  // ---- fragment read offsets: lane -> row lane%32 of a 32-row group, 16-byte chunk (2*kk + lane/32)
+  // fragment reads: lane -> row lane%32 of a 32-row group, logical chunk 2*kk + lane/32
+  const uint32_t sw = (uint32_t)(lane & 7);
   const uint32_t fragA = (uint32_t)((wp * WTP + (lane & 31)) * kRowBytes);
   const uint32_t fragB = (uint32_t)((wq * WTQ + (lane & 31)) * kRowBytes);
+
   // ---- steps.  A phase is one tensor (K or V) of the whole block (MODE 0) or of one head
   // (MODE 1).  Step u of a phase reads 128 bytes per block at byte offset
-  // base + (u/2)*tok + (u%2)*128:  tok = 256, base = 0 walks the flattened block; tok = H*256,
-  // base = head*256 walks one head's [T][Dh] slice.
+  // head*256 + (u/2)*tok + (u%2)*128:  tok = 256 walks the flattened block, tok = H*256 walks
+  // one head's [T][Dh] slice.
   const int sps = (MODE == 0) ? (D / kBK) : (p.T * 2);
+  const int nphase = (MODE == 0) ? 2 : 2 * p.H;
   const int tok = (MODE == 0) ? 256 : p.H * 256;
-  auto step_off = [&](int base, int u) { return base + (u >> 1) * tok + (u & 1) * 128; };
-
-  auto issue = [&](const __amdgpu_buffer_rsrc_t ra, const __amdgpu_buffer_rsrc_t rb, int off, char* dA, char* dB) {
-#pragma unroll
-    for (int i = 0; i < LA; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, RC_LDS_PTR(dA + (i * NT + wave * 64) * 16), 16, offA[i], off, 0, 0);
-#pragma unroll
-    for (int i = 0; i < LB; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, RC_LDS_PTR(dB + (i * NT + wave * 64) * 16), 16, offB[i], off, 0, 0);
+  auto advance = [&](Cursor& c) {
+    if (++c.u == sps) {
+      c.u = 0;
+      ++c.ph;
+    }
   };
+  auto byte_off = [&](const Cursor& c) { return (uint32_t)((c.ph >> 1) * 256 + (c.u >> 1) * tok + (c.u & 1) * 128); };
+
+  // Where the next pool / query slice comes from and which ring stage it goes to.  Past the last
+  // step the cursor stays on the last slice: the two refills that nobody needs re-read valid
+  // data, so every step issues the same number of loads and the wait counts stay uniform.
+  struct Feed {
+    Cursor cur;
+    int stage;
+    i32x4 srd;
+    uint32_t off, dst;
+  };
+  Feed fa{{0, 0}, 0, srdAk, 0, 0}, fb{{0, 0}, 0, srdBk, 0, 0};
+  auto prepare = [&](Feed& f, const i32x4& k_srd, const i32x4& v_srd, uint32_t ring, int stage_bytes) {
+    f.srd = (f.cur.ph & 1) ? v_srd : k_srd;
+    f.off = byte_off(f.cur);
+    f.dst = ring + f.stage * stage_bytes + wave * 1024;
+  };
+  auto next = [&](Feed& f, int stages) {
+    Cursor n = f.cur;
+    advance(n);
+    if (n.ph < nphase) f.cur = n;
+    f.stage = (f.stage + 1 == stages) ? 0 : f.stage + 1;
+  };
+  auto dmaA = [&](int i) { dma16(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16); };
+  auto dmaB = [&](int i) { dma16(fb.srd, voff, fb.off + i * load_stride, fb.dst + i * NT * 16); };
 
   f32x16 acc[TP][TQ];
 #pragma unroll
@@ -174,89 +245,130 @@ __global__ __launch_bounds__(64 * WP * WQ, MINBLK) void match_tile_kernel(const 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // Fragments of sub-step kk+1 are requested before the matrix instructions of sub-step kk are
-  // issued; the scheduling barriers keep the compiler from hoisting every read to the top.
+  // One step = 4 sub-steps of 16 reduction elements = 4 batches of TP*TQ matrix instructions.
+  //  - Fragments of a sub-step are requested one batch before they are multiplied.
+  //  - The last batch of a step is issued after the next step's barrier: its fragments are
+  //    already in registers, so the matrix cores have work while the first fragment reads of
+  //    the new step are in flight.
+  //  - The step's LB + LA refill loads are spread between the matrix instructions (query slice
+  //    first): the texture unit takes a 1 KB wave load every 16 cycles, and a wave that issues
+  //    its loads in one burst sits in that queue instead of feeding the matrix cores.
+  // The scheduling barriers pin this order.
+  constexpr int SLOTS = 4 * TP, LPS = (LA + LB + SLOTS - 1) / SLOTS;
   auto load_frags = [&](const char* sA, const char* sB, int kk, uint4 (&af)[TP], uint4 (&bf)[TQ]) {
-    const uint32_t c = (uint32_t)(((2 * kk + (lane >> 5)) ^ (lane & 7)) * 16);
+    const uint32_t c = (((uint32_t)(2 * kk) + (uint32_t)(lane >> 5)) ^ sw) * 16;
 #pragma unroll
     for (int i = 0; i < TP; ++i) af[i] = *reinterpret_cast<const uint4*>(sA + fragA + i * 32 * kRowBytes + c);
 #pragma unroll
     for (int j = 0; j < TQ; ++j) bf[j] = *reinterpret_cast<const uint4*>(sB + fragB + j * 32 * kRowBytes + c);
   };
-  auto compute = [&](const char* sA, const char* sB) {
-    uint4 af[2][TP], bf[2][TQ];
-    load_frags(sA, sB, 0, af[0], bf[0]);
+  auto batch = [&](const uint4 (&af)[TP], const uint4 (&bf)[TQ], int b) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      if (kk + 1 < 4) load_frags(sA, sB, kk + 1, af[(kk + 1) & 1], bf[(kk + 1) & 1]);
+    for (int i = 0; i < TP; ++i) {
 #pragma unroll
-      for (int i = 0; i < TP; ++i)
+      for (int j = 0; j < TQ; ++j) {
+        acc[i][j] = mfma<BF16>(af[i], bf[j], acc[i][j]);
+        if (j == TQ - 1) {
 #pragma unroll
-        for (int j = 0; j < TQ; ++j) acc[i][j] = mfma<BF16>(af[kk & 1][i], bf[kk & 1][j], acc[i][j]);
+          for (int t = 0; t < LPS; ++t) {
+            const int n = (b * TP + i) * LPS + t;
+            if (n < LB)
+              dmaB(n);
+            else if (n < LB + LA)
+              dmaA(n - LB);
+          }
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-
-  // ---- scale factors of the current head (or of the whole block) into LDS
-  auto load_scales = [&](int head) {
-    const int nh = (MODE == 0) ? 1 : p.H;
-    for (int r = tid; r < BP; r += NT) {
-      const int gp = p0 + r;
-      float rp = 0.f, fp = 0.f, bias = -INFINITY;
-      if (gp < p.P) {
-        const long long o = ((long long)l * p.P + gp) * nh + head;
-        const float ak = inv_sqrt_or(p.p_ksq[o], 0.f), av = inv_sqrt_or(p.p_vsq[o], 1.f);
-        rp = ak / av;
-        fp = av;
-        if (!p.live || p.live[(long long)l * p.P + gp]) bias = 0.f;
-      }
-      s_rp[r] = rp;
-      s_fp[r] = fp;
-      s_bias[r] = bias;
-    }
-    for (int c = tid; c < BQ; c += NT) {
-      const int gq = q0 + c;
-      float rq = 0.f, fq = 0.f;
-      if (gq < p.Q) {
-        const long long o = ((long long)l * p.Q + gq) * nh + head;
-        const float ak = inv_sqrt_or(p.q_ksq[o], 0.f), av = inv_sqrt_or(p.q_vsq[o], 1.f);
-        rq = ak / av;
-        fq = 0.5f * av;
-      }
-      s_rq[c] = rq;
-      s_fq[c] = fq;
-    }
+  uint4 fwA[TP], fwB[TQ];  // fragments of the previous step's last sub-step, not multiplied yet
+  auto clear_pending = [&]() {
+#pragma unroll
+    for (int i = 0; i < TP; ++i) fwA[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < TQ; ++j) fwB[j] = make_uint4(0, 0, 0, 0);
+  };
+  auto compute = [&](const char* sA, const char* sB) {
+    uint4 fa0[TP], fb0[TQ], fa1[TP], fb1[TQ];
+    load_frags(sA, sB, 0, fa0, fb0);
+    batch(fwA, fwB, 0);  // previous step, sub-step 3 (zeros at the start of a phase)
+    load_frags(sA, sB, 1, fa1, fb1);
+    batch(fa0, fb0, 1);
+    load_frags(sA, sB, 2, fa0, fb0);
+    batch(fa1, fb1, 2);
+    load_frags(sA, sB, 3, fwA, fwB);
+    batch(fa0, fb0, 3);
+  };
+  // multiply what is still pending (end of a phase); no refills ride on these instructions
+  auto drain = [&]() {
+#pragma unroll
+    for (int i = 0; i < TP; ++i)
+#pragma unroll
+      for (int j = 0; j < TQ; ++j) acc[i][j] = mfma<BF16>(fwA[i], fwB[j], acc[i][j]);
   };
 
+  // ---- scale factors, read from the cached squared norms when a phase ends.  Range-checked
+  // buffer loads with 32-bit offsets: a row past the end of the pool / queries reads 0.
+  const int nh = (MODE == 0) ? 1 : p.H;
+  const __amdgpu_buffer_rsrc_t nQk = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q_ksq + (long long)l * p.Q * nh), 0, p.Q * nh * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t nQv = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q_vsq + (long long)l * p.Q * nh), 0, p.Q * nh * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t nPk = __builtin_amdgcn_make_buffer_rsrc((void*)(p.p_ksq + (long long)l * p.P * nh), 0, p.P * nh * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t nPv = __builtin_amdgcn_make_buffer_rsrc((void*)(p.p_vsq + (long long)l * p.P * nh), 0, p.P * nh * 4, 0x00020000);
+  // Query column j of this lane: ratio rq = aK/aV and final factor fq = aV/2.
+  auto query_scales = [&](int head, float (&rq)[TQ], float (&fq)[TQ]) {
+#pragma unroll
+    for (int j = 0; j < TQ; ++j) {
+      const int o = ((q0 + wq * WTQ + j * 32 + (lane & 31)) * nh) * 4;
+      const float ksq = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nQk, o, head * 4, 0));
+      const float vsq = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nQv, o, head * 4, 0));
+      float av;
+      norm_factors(ksq, vsq, rq[j], av);
+      fq[j] = 0.5f * av;
+    }
+  };
+  // Pool rows row .. row+3 of the tile: ratio rp = aK/aV and final factor fp = aV.
+  auto pool_scales = [&](int row, int head, f32x4& rp, f32x4& fp) {
+    f32x4 ksq, vsq;
+    if (MODE == 0) {
+      typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+      ksq = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nPk, (p0 + row) * 4, 0, 0));
+      vsq = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nPv, (p0 + row) * 4, 0, 0));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int o = (p0 + row + e) * nh * 4;
+        ksq[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nPk, o, head * 4, 0));
+        vsq[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nPv, o, head * 4, 0));
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float ratio, av;
+      norm_factors(ksq[e], vsq[e], ratio, av);
+      rp[e] = ratio;
+      fp[e] = av;
+    }
+  };
   // rows of accumulator register group g (4 registers) of row tile i: wp*WTP + i*32 + 8*g + 4*(lane/32) + 0..3
   auto row_of = [&](int i, int g) { return wp * WTP + i * 32 + 8 * g + 4 * (lane >> 5); };
 
-  // the 16 pool-row factors of row tile i as one register tuple, matching an accumulator tile
-  auto row_vec = [&](const float* tab, int i) {
-    f32x16 v;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const f32x4 t = *reinterpret_cast<const f32x4*>(&tab[row_of(i, g)]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[4 * g + e] = t[e];
-    }
-    return v;
-  };
-
   // acc <- acc * (rq * rp)   (end of a K phase)
-  auto rescale = [&]() {
-    float rq[TQ];
+  auto rescale = [&](int head) {
+    float rq[TQ], fq[TQ];
+    query_scales(head, rq, fq);
 #pragma unroll
-    for (int j = 0; j < TQ; ++j) rq[j] = s_rq[wq * WTQ + j * 32 + (lane & 31)];
+    for (int i = 0; i < TP; ++i)
 #pragma unroll
-    for (int i = 0; i < TP; ++i) {
-      const f32x16 rp = row_vec(s_rp, i);
+      for (int g = 0; g < 4; ++g) {
+        f32x4 rp, fp;
+        pool_scales(row_of(i, g), head, rp, fp);
 #pragma unroll
-      for (int j = 0; j < TQ; ++j) {
-        acc[i][j] = acc[i][j] * (rp * rq[j]);
-        __builtin_amdgcn_sched_barrier(0);  // one tile at a time keeps the register pressure low
+        for (int j = 0; j < TQ; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] *= rq[j] * rp[e];
+        __builtin_amdgcn_sched_barrier(0);  // one register group at a time keeps the pressure low
       }
-    }
   };
 
   // per-head mode: running minimum over heads of the finished head score; acc restarts at 0
@@ -269,68 +381,97 @@ __global__ __launch_bounds__(64 * WP * WQ, MINBLK) void match_tile_kernel(const 
 #pragma unroll
         for (int r = 0; r < 16; ++r) smin[i][j][r] = INFINITY;
   }
-  auto finish_head = [&]() {
-    float fq[TQ];
-#pragma unroll
-    for (int j = 0; j < TQ; ++j) fq[j] = s_fq[wq * WTQ + j * 32 + (lane & 31)];
+  auto finish_head = [&](int head) {
+    float rq[TQ], fq[TQ];
+    query_scales(head, rq, fq);
 #pragma unroll
     for (int i = 0; i < TP; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const f32x4 fp = *reinterpret_cast<const f32x4*>(&s_fp[row_of(i, g)]);
+        f32x4 rp, fp;
+        pool_scales(row_of(i, g), head, rp, fp);
 #pragma unroll
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float s = acc[i][j][4 * g + e] * (fq[j] * fp[e]);
+            const float sc = acc[i][j][4 * g + e] * (fq[j] * fp[e]);
             smin[MODE == 0 ? 0 : i][MODE == 0 ? 0 : j][4 * g + e] =
-                fminf(smin[MODE == 0 ? 0 : i][MODE == 0 ? 0 : j][4 * g + e], s);
+                fminf(smin[MODE == 0 ? 0 : i][MODE == 0 ? 0 : j][4 * g + e], sc);
             acc[i][j][4 * g + e] = 0.f;
           }
         __builtin_amdgcn_sched_barrier(0);
       }
   };
 
-  // ---- main loop: two-stage ring, one barrier per step.  The loads of step u+1 are issued
-  // right after the barrier of step u; the last step of a phase issues the first step of the
-  // next phase, so the ring never drains between phases.
-  auto run_phase = [&](const __amdgpu_buffer_rsrc_t ra, const __amdgpu_buffer_rsrc_t rb, int base,
-                       const __amdgpu_buffer_rsrc_t na, const __amdgpu_buffer_rsrc_t nb, int nbase, bool has_next) {
-    for (int u = 0; u < sps; u += 2) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my loads of step u are in LDS
-      __syncthreads();                                  // everyone's are, and stage 1 is free
-      issue(ra, rb, step_off(base, u + 1), sA1, sB1);
-      compute(sA0, sB0);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      if (u + 2 < sps)
-        issue(ra, rb, step_off(base, u + 2), sA0, sB0);
-      else if (has_next)
-        issue(na, nb, step_off(nbase, 0), sA0, sB0);
-      compute(sA1, sB1);
+  // ---- main loop.  Per step: wait for this step's slices, barrier, then compute while refilling
+  // the stages the barrier has just freed (query slice of the next step, pool slice of the step
+  // after).  The query loads are issued before the pool loads, so "at most LA loads outstanding"
+  // means exactly: everything but the newest pool slice has landed.
+  // prologue: query slice 0, pool slices 0 and 1; then the feeds point at query slice 1, pool slice 2
+  prepare(fb, srdBk, srdBv, ringB, B_STAGE);
+#pragma unroll
+  for (int i = 0; i < LB; ++i) dmaB(i);
+  next(fb, SB);
+  for (int k = 0; k < 2; ++k) {
+    prepare(fa, srdAk, srdAv, ringA, A_STAGE);
+#pragma unroll
+    for (int i = 0; i < LA; ++i) dmaA(i);
+    next(fa, SA);
+  }
+  int rdA = 0, rdB = 0;
+#ifdef RC_PROFILE_STEPS
+  const long long mt0 = __builtin_amdgcn_s_memtime(), wc0 = wall_clock64();
+  long long t_wait = 0, t_bar = 0, t_issue = 0, t_comp = 0;
+#define RC_T(x) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); x = __builtin_amdgcn_s_memtime(); }
+#else
+#define RC_T(x)
+#endif
+  auto run_phase = [&]() {
+    clear_pending();
+    for (int u = 0; u < sps; ++u) {
+#ifdef RC_PROFILE_STEPS
+      long long c0, c1, c2, c3, c4;
+#endif
+      RC_T(c0)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LA) : "memory");  // all but the newest pool slice landed
+      RC_T(c1)
+      __syncthreads();  // ... for every wave, and the stages read in the previous step are free
+      RC_T(c2)
+      prepare(fb, srdBk, srdBv, ringB, B_STAGE);
+      prepare(fa, srdAk, srdAv, ringA, A_STAGE);
+      RC_T(c3)
+      compute(s_ring + rdA * A_STAGE, s_ring + SA * A_STAGE + rdB * B_STAGE);
+      next(fb, SB);
+      next(fa, SA);
+#ifdef RC_PROFILE_STEPS
+      asm volatile("s_nop 0" ::: "memory");
+      c4 = __builtin_amdgcn_s_memtime();
+      t_wait += c1 - c0; t_bar += c2 - c1; t_issue += c3 - c2; t_comp += c4 - c3;
+#endif
+      rdA = (rdA + 1 == SA) ? 0 : rdA + 1;
+      rdB = (rdB + 1 == SB) ? 0 : rdB + 1;
     }
+    drain();
   };
-
-  load_scales(0);
-  issue(resA[0], resB[0], step_off(0, 0), sA0, sB0);
   if (MODE == 0) {
-    run_phase(resA[0], resB[0], 0, resA[1], resB[1], 0, true);
-    rescale();
-    run_phase(resA[1], resB[1], 0, resA[1], resB[1], 0, false);
+    run_phase();
+    rescale(0);
+    run_phase();
   } else {
     for (int h = 0; h < p.H; ++h) {
-      run_phase(resA[0], resB[0], h * 256, resA[1], resB[1], h * 256, true);
-      rescale();
-      run_phase(resA[1], resB[1], h * 256, resA[0], resB[0], (h + 1) * 256, h + 1 < p.H);
-      finish_head();
-      if (h + 1 < p.H) {
-        __syncthreads();  // every wave is done with this head's scales
-        load_scales(h + 1);
-        // the barriers of the next phase make the new scales visible before they are read
-      }
+      run_phase();
+      rescale(h);
+      run_phase();
+      finish_head(h);
     }
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus refills of the last steps have landed
 
+#ifdef RC_PROFILE_STEPS
+  if ((tile == 0 || tile == p.total / 2) && lane == 0)
+    printf("tile %d wave %d: wait %lld barrier %lld issue %lld compute %lld (%d steps) memtime %lld wallclock(100MHz) %lld\n", tile, wave,
+           t_wait, t_bar, t_issue, t_comp, sps * nphase, (long long)__builtin_amdgcn_s_memtime() - mt0, (long long)wall_clock64() - wc0);
+#endif
   // ---- tile epilogue: scores, dead/tail masking, top-2 per query column
   float best[TQ], second[TQ];
   int bidx[TQ];
@@ -341,16 +482,20 @@ __global__ __launch_bounds__(64 * WP * WQ, MINBLK) void match_tile_kernel(const 
     bidx[j] = -1;
   }
   {
-    float fq[TQ];
-#pragma unroll
-    for (int j = 0; j < TQ; ++j) fq[j] = s_fq[wq * WTQ + j * 32 + (lane & 31)];
+    float rq[TQ], fq[TQ];
+    if (MODE == 0) query_scales(0, rq, fq);
 #pragma unroll
     for (int i = 0; i < TP; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int row = row_of(i, g);
-        const f32x4 fp = *reinterpret_cast<const f32x4*>(&s_fp[row]);
-        const f32x4 bias = *reinterpret_cast<const f32x4*>(&s_bias[row]);
+        f32x4 rp, fp, bias;
+        if (MODE == 0) pool_scales(row, 0, rp, fp);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int gp = p0 + row + e;
+          bias[e] = (gp < p.P && (!p.live || p.live[(long long)l * p.P + gp])) ? 0.f : -INFINITY;
+        }
 #pragma unroll
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
@@ -373,6 +518,8 @@ __global__ __launch_bounds__(64 * WP * WQ, MINBLK) void match_tile_kernel(const 
     const float s2 = __shfl_xor(second[j], 32);
     top2_merge(best[j], bidx[j], second[j], b2, i2, s2);
   }
+  __syncthreads();  // every wave is done reading the ring: its first bytes become the merge scratch
+  Part* s_part = reinterpret_cast<Part*>(s_ring);  // [WP][BQ]
   if (lane < 32) {
 #pragma unroll
     for (int j = 0; j < TQ; ++j) {
@@ -381,15 +528,15 @@ __global__ __launch_bounds__(64 * WP * WQ, MINBLK) void match_tile_kernel(const 
       t.idx = bidx[j];
       t.second = second[j];
       t.pad = 0;
-      s_part[wp][wq * WTQ + j * 32 + lane] = t;
+      s_part[wp * BQ + wq * WTQ + j * 32 + lane] = t;
     }
   }
   __syncthreads();
   if (tid < BQ && q0 + tid < p.Q) {
-    Part t = s_part[0][tid];
+    Part t = s_part[tid];
 #pragma unroll
     for (int w = 1; w < WP; ++w) {
-      const Part u = s_part[w][tid];
+      const Part u = s_part[w * BQ + tid];
       top2_merge(t.best, t.idx, t.second, u.best, u.idx, u.second);
     }
     p.part[((long long)l * p.npt + pt) * p.Q + q0 + tid] = t;
@@ -434,9 +581,9 @@ inline TileShape tile_for(int mode) { return mode == RC_SCORE_BLOCK ? kBlockTile
 template <bool BF16>
 void launch_tiles(int mode, const MatchParams& mp, unsigned grid, hipStream_t st) {
   if (mode == RC_SCORE_BLOCK)
-    match_tile_kernel<BF16, kBlockTile.bp, kBlockTile.bq, 2, 2, 0, 1><<<grid, 256, 0, st>>>(mp);
+    match_tile_kernel<BF16, kBlockTile.bp, kBlockTile.bq, 0><<<grid, kThreads, 0, st>>>(mp);
   else
-    match_tile_kernel<BF16, kHeadTile.bp, kHeadTile.bq, 2, 2, 1, 1><<<grid, 256, 0, st>>>(mp);
+    match_tile_kernel<BF16, kHeadTile.bp, kHeadTile.bq, 1><<<grid, kThreads, 0, st>>>(mp);
 }
 
 }  // namespace
