@@ -18,6 +18,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # dense MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of match_tile_kernel from rocprofv3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scales
+# that the 1 GiB copy at the start of this script gives); see profiles/bench_cfg2_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"cfg2_qwq32b_step": 18.53e9}
 
 
 def log(msg):
@@ -70,6 +73,14 @@ def main():
     pr = synth.make_problem(w, dev)
     torch.cuda.synchronize()
     log(f"inputs resident ({(w.L * (w.P + w.Q) * w.block_bytes) / 1e9:.1f} GB of KV) after {time.time() - t0:.1f} s")
+
+    # a plain device-to-device copy of known size: the yardstick that scales the profiler's
+    # FETCH_SIZE / WRITE_SIZE counters into bytes
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
 
     L, P, Q = w.L, w.P, w.Q
     # pool norms: computed when the blocks were sealed, cached since (also timed once, as the cold fill)
@@ -133,7 +144,8 @@ def main():
     match_tflops = flop / (match_ms * 1e-3) / 1e12
     roofline = {"kernel": "match_tile_kernel (inside rc_match_blocks)", "bound": "mfma",
                 "achieved": match_tflops, "peak": PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
-                "frac": match_tflops / PEAK_TFLOPS[w.dtype], "traffic": None}
+                "frac": match_tflops / PEAK_TFLOPS[w.dtype],
+                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if not args.layers else None}
     match_gbs = kv_bytes / (match_ms * 1e-3) / 1e9
     qnorm_bytes = L * Q * w.block_bytes
     remap_bytes = L * (2 * w.R * w.E * 4 + 2 * w.NB * 4)
