@@ -23,6 +23,10 @@
 
 #include "rc_common.hpp"
 
+#ifndef RC_POOL_WAVES
+#define RC_POOL_WAVES 2
+#endif
+
 namespace rc {
 namespace {
 
@@ -34,7 +38,8 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;             // reduction elements per pipeline step
 constexpr int kRowBytes = kBK * 2;  // bytes of one block's slice in LDS (one 128-byte line)
-constexpr int kThreads = 256;       // 4 waves as 2 (pool) x 2 (query)
+constexpr int kPoolWaves = RC_POOL_WAVES, kQueryWaves = 2;  // waves of a workgroup along the two tile sides
+constexpr int kThreads = 64 * kPoolWaves * kQueryWaves;
 constexpr int kPoolStages = 3, kQueryStages = 2;
 
 // Partial selection result of one pool tile for one query.
@@ -137,7 +142,7 @@ struct Cursor {
 template <bool BF16, int BP, int BQ, int MODE>
 __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
-  constexpr int NT = kThreads, WP = 2, WQ = 2;
+  constexpr int NT = kThreads, WP = kPoolWaves, WQ = kQueryWaves;
   constexpr int WTP = BP / WP, WTQ = BQ / WQ;
   constexpr int TP = WTP / 32, TQ = WTQ / 32;
   constexpr int LA = BP * 8 / NT, LB = BQ * 8 / NT;  // 16-byte loads per thread per step
