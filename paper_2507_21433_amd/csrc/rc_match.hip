@@ -23,10 +23,6 @@
 
 #include "rc_common.hpp"
 
-#ifndef RC_POOL_WAVES
-#define RC_POOL_WAVES 2
-#endif
-
 namespace rc {
 namespace {
 
@@ -38,7 +34,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;             // reduction elements per pipeline step
 constexpr int kRowBytes = kBK * 2;  // bytes of one block's slice in LDS (one 128-byte line)
-constexpr int kPoolWaves = RC_POOL_WAVES, kQueryWaves = 2;  // waves of a workgroup along the two tile sides
+constexpr int kPoolWaves = 2, kQueryWaves = 2;  // waves of a workgroup along the two tile sides
 constexpr int kThreads = 64 * kPoolWaves * kQueryWaves;
 constexpr int kPoolStages = 3, kQueryStages = 2;
 
@@ -424,35 +420,16 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     next(fa, SA);
   }
   int rdA = 0, rdB = 0;
-#ifdef RC_PROFILE_STEPS
-  const long long mt0 = __builtin_amdgcn_s_memtime(), wc0 = wall_clock64();
-  long long t_wait = 0, t_bar = 0, t_issue = 0, t_comp = 0;
-#define RC_T(x) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); x = __builtin_amdgcn_s_memtime(); }
-#else
-#define RC_T(x)
-#endif
   auto run_phase = [&]() {
     clear_pending();
     for (int u = 0; u < sps; ++u) {
-#ifdef RC_PROFILE_STEPS
-      long long c0, c1, c2, c3, c4;
-#endif
-      RC_T(c0)
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LA) : "memory");  // all but the newest pool slice landed
-      RC_T(c1)
       __syncthreads();  // ... for every wave, and the stages read in the previous step are free
-      RC_T(c2)
       prepare(fb, srdBk, srdBv, ringB, B_STAGE);
       prepare(fa, srdAk, srdAv, ringA, A_STAGE);
-      RC_T(c3)
       compute(s_ring + rdA * A_STAGE, s_ring + SA * A_STAGE + rdB * B_STAGE);
       next(fb, SB);
       next(fa, SA);
-#ifdef RC_PROFILE_STEPS
-      asm volatile("s_nop 0" ::: "memory");
-      c4 = __builtin_amdgcn_s_memtime();
-      t_wait += c1 - c0; t_bar += c2 - c1; t_issue += c3 - c2; t_comp += c4 - c3;
-#endif
       rdA = (rdA + 1 == SA) ? 0 : rdA + 1;
       rdB = (rdB + 1 == SB) ? 0 : rdB + 1;
     }
@@ -472,11 +449,6 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus refills of the last steps have landed
 
-#ifdef RC_PROFILE_STEPS
-  if ((tile == 0 || tile == p.total / 2) && lane == 0)
-    printf("tile %d wave %d: wait %lld barrier %lld issue %lld compute %lld (%d steps) memtime %lld wallclock(100MHz) %lld\n", tile, wave,
-           t_wait, t_bar, t_issue, t_comp, sps * nphase, (long long)__builtin_amdgcn_s_memtime() - mt0, (long long)wall_clock64() - wc0);
-#endif
   // ---- tile epilogue: scores, dead/tail masking, top-2 per query column
   float best[TQ], second[TQ];
   int bidx[TQ];

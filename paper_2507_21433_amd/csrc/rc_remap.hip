@@ -2,13 +2,15 @@
 // (ReasonCache Sec. IV-B: the kept block's reference count goes up, the table entry is
 // rewritten, nothing is copied; a block is freed only at reference count 0).
 //
-// Four stream-ordered launches, no atomics anywhere:
-//   1. prepare : slot_of[b] = -1 for every physical block, refcount_out = refcount_in
-//   2. scatter : slot_of[query_ids[q]] = q
-//   3. gather  : table_out[e] = target of table_in[e]; references to matched query blocks are
-//                counted per workgroup in an LDS histogram that one wave at a time updates
-//                (equal keys inside a wave are merged with ballots), then stored as partials
-//   4. finalize: per layer, cnt[q] = sum of partials; the query block loses cnt references,
+// Three stream-ordered launches, no atomics anywhere:
+//   1. scatter : slot_of[query_ids[q]] = q.  slot_of is never cleared: an entry s read for block b
+//                counts only if s < Q and query_ids[s] == b, so stale or uninitialised words are harmless
+//   2. gather  : table_out[e] = target of table_in[e] (16-byte loads and stores when the layout
+//                allows); references to matched query blocks are counted per workgroup in an LDS
+//                histogram that one wave at a time updates (equal keys inside a wave are merged
+//                with ballots), then stored as partials; the same workgroups copy their share of
+//                refcount_in to refcount_out
+//   3. finalize: per layer, cnt[q] = sum of partials; the query block loses cnt references,
 //                its target gains them.  Queries that share a target take turns through a
 //                small claim table in LDS, one winner per slot and round.
 #include <hip/hip_runtime.h>
@@ -26,22 +28,16 @@ constexpr int kFinalThreads = 1024;
 constexpr int kFinalPerThread = kMaxQ / kFinalThreads;
 constexpr int kClaimSlots = 4096;
 
-// How the R*E entries of a layer are cut into workgroups: large enough chunks that the
-// per-workgroup partial histogram (Q ints) stays a small fraction of the table traffic.
-inline int64_t chunks_per_layer(int64_t RE, int64_t Q) {
-  const int64_t min_chunk = (4 * Q > kGatherBatch) ? 4 * Q : kGatherBatch;
-  int64_t g = RE / min_chunk;
+// How the R*E entries of a layer are cut into workgroups: about 1024 workgroups over all layers
+// when the tables are small (to fill 256 compute units), one per layer when there are many layers
+// (so the per-workgroup partial histogram of Q ints stays a small fraction of the table traffic).
+inline int64_t chunks_per_layer(int64_t RE, int64_t L) {
+  int64_t g = (1024 + L - 1) / (L > 0 ? L : 1);
+  const int64_t most = RE / kGatherBatch;
+  if (g > most) g = most;
   if (g < 1) g = 1;
   if (g > 65535) g = 65535;
   return g;
-}
-
-__global__ __launch_bounds__(256) void remap_prepare_kernel(int32_t* __restrict__ slot_of, long long NB,
-                                                            const int32_t* refcount_in, int32_t* refcount_out,
-                                                            long long LNB) {
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < NB) slot_of[i] = -1;
-  if (i < LNB && refcount_in != refcount_out) refcount_out[i] = refcount_in[i];
 }
 
 __global__ __launch_bounds__(256) void remap_scatter_kernel(int32_t* __restrict__ slot_of,
@@ -53,12 +49,33 @@ __global__ __launch_bounds__(256) void remap_scatter_kernel(int32_t* __restrict_
   }
 }
 
-// grid = (G, L).  Workgroup g rewrites entries [g*chunk, min((g+1)*chunk, RE)) of layer l.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Query slot of physical block t, or -1.  slot_of may hold anything; a slot counts only if it
+// points back at t.  A matched slot is then replaced by its target (out) and kept for counting.
+__device__ __forceinline__ int remap_entry(int t, const int32_t* __restrict__ slot_of,
+                                           const int32_t* __restrict__ query_ids, const int32_t* __restrict__ pool_ids,
+                                           const int32_t* __restrict__ m, int Q, int P, long long NB, int& slot) {
+  slot = -1;
+  if (t < 0 || t >= NB) return t;
+  const int s = slot_of[t];
+  if ((unsigned)s >= (unsigned)Q || query_ids[s] != t) return t;
+  const int mi = m[s];
+  if (mi < 0 || mi >= P) return t;  // unmatched query block: entry stays, nothing to count
+  slot = s;
+  return pool_ids ? pool_ids[mi] : mi;
+}
+
+// grid = (G, L).  Workgroup g rewrites entries [g*chunk, min((g+1)*chunk, RE)) of layer l and copies
+// refcounts [g*rc_chunk, ...) of the layer.  VEC: every layer starts 16-byte aligned and chunk % 4 == 0.
+template <bool VEC>
 __global__ __launch_bounds__(kGatherThreads) void remap_gather_kernel(
     const int32_t* tables_in, int32_t* tables_out, long long RE, long long chunk,
-    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ pool_ids,
-    const int32_t* __restrict__ match_idx, int Q, int P, long long NB, int32_t* __restrict__ partial) {
-  __shared__ int hist[kMaxQ];
+    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ query_ids,
+    const int32_t* __restrict__ pool_ids, const int32_t* __restrict__ match_idx, int Q, int P, long long NB,
+    int32_t* __restrict__ partial, const int32_t* refcount_in, int32_t* refcount_out, long long rc_chunk,
+    int rc_vec) {
+  extern __shared__ int hist[];  // Q bins
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long l = blockIdx.y, g = blockIdx.x, G = gridDim.x;
   for (int q = tid; q < Q; q += kGatherThreads) hist[q] = 0;
@@ -70,28 +87,55 @@ __global__ __launch_bounds__(kGatherThreads) void remap_gather_kernel(
 
   for (long long base = lo; base < hi; base += kGatherBatch) {
     int entry[kGatherPerThread], slot[kGatherPerThread];
+    // thread -> 4 consecutive entries per load (VEC) or entries strided by the workgroup size
+    auto index_of = [&](int k) {
+      return VEC ? base + ((k >> 2) * kGatherThreads + tid) * 4 + (k & 3) : base + (long long)k * kGatherThreads + tid;
+    };
+    if (VEC) {
 #pragma unroll
-    for (int k = 0; k < kGatherPerThread; ++k) {
-      const long long e = base + k * kGatherThreads + tid;
-      entry[k] = (e < hi) ? tin[e] : -1;
-    }
+      for (int k = 0; k < kGatherPerThread; k += 4) {
+        const long long e = index_of(k);
+        i32x4 v = {-1, -1, -1, -1};
+        if (e + 3 < hi) {
+          v = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(tin + e));
+        } else {
 #pragma unroll
-    for (int k = 0; k < kGatherPerThread; ++k) {
-      const int t = entry[k];
-      slot[k] = (t >= 0 && t < NB) ? slot_of[t] : -1;
-    }
+          for (int c = 0; c < 4; ++c)
+            if (e + c < hi) v[c] = tin[e + c];
+        }
 #pragma unroll
-    for (int k = 0; k < kGatherPerThread; ++k) {
-      int out = entry[k];
-      if (slot[k] >= 0) {
-        const int mi = m[slot[k]];
-        if (mi >= 0 && mi < P)
-          out = pool_ids ? pool_ids[mi] : mi;
-        else
-          slot[k] = -1;  // unmatched query block: entry stays, nothing to count
+        for (int c = 0; c < 4; ++c) entry[k + c] = v[c];
       }
-      const long long e = base + k * kGatherThreads + tid;
-      if (e < hi) tout[e] = out;
+    } else {
+#pragma unroll
+      for (int k = 0; k < kGatherPerThread; ++k) {
+        const long long e = index_of(k);
+        entry[k] = (e < hi) ? tin[e] : -1;
+      }
+    }
+    int outv[kGatherPerThread];
+#pragma unroll
+    for (int k = 0; k < kGatherPerThread; ++k)
+      outv[k] = remap_entry(entry[k], slot_of, query_ids, pool_ids, m, Q, P, NB, slot[k]);
+    if (VEC) {
+#pragma unroll
+      for (int k = 0; k < kGatherPerThread; k += 4) {
+        const long long e = index_of(k);
+        if (e + 3 < hi) {
+          i32x4 v = {outv[k], outv[k + 1], outv[k + 2], outv[k + 3]};
+          __builtin_nontemporal_store(v, reinterpret_cast<i32x4*>(tout + e));
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (e + c < hi) tout[e + c] = outv[k + c];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < kGatherPerThread; ++k) {
+        const long long e = index_of(k);
+        if (e < hi) tout[e] = outv[k];
+      }
     }
     // count the rewritten references, one wave at a time
     bool any = false;
@@ -115,6 +159,24 @@ __global__ __launch_bounds__(kGatherThreads) void remap_gather_kernel(
         }
         __syncthreads();
       }
+    }
+  }
+  // this workgroup's share of the refcount copy (the finalize kernel then edits refcount_out)
+  if (refcount_in != refcount_out) {
+    const long long rlo = g * rc_chunk, rhi = (rlo + rc_chunk < NB) ? rlo + rc_chunk : NB;
+    const int32_t* src = refcount_in + l * NB;
+    int32_t* dst = refcount_out + l * NB;
+    if (rc_vec) {
+      for (long long i = rlo + tid * 4LL; i < rhi; i += kGatherThreads * 4LL) {
+        if (i + 3 < rhi) {
+          __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src + i)),
+                                      reinterpret_cast<i32x4*>(dst + i));
+        } else {
+          for (long long c = i; c < rhi; ++c) dst[c] = src[c];
+        }
+      }
+    } else {
+      for (long long i = rlo + tid; i < rhi; i += kGatherThreads) dst[i] = src[i];
     }
   }
   __syncthreads();
@@ -200,7 +262,7 @@ __global__ __launch_bounds__(kFinalThreads) void remap_finalize_kernel(
 extern "C" size_t rc_remap_workspace_size(int32_t n_layers, int64_t R, int64_t E, int64_t Q, int64_t NB) {
   using namespace rc;
   if (n_layers < 0 || R < 0 || E < 0 || Q < 0 || NB < 0) return 0;
-  const int64_t G = chunks_per_layer(R * E, Q);
+  const int64_t G = chunks_per_layer(R * E, n_layers);
   const int64_t ints = ((NB + 3) / 4) * 4 + (int64_t)n_layers * G * Q;
   return (size_t)(ints > 0 ? ints : 4) * sizeof(int32_t);
 }
@@ -231,20 +293,28 @@ extern "C" rc_status rc_remap_block_table(int32_t n_layers, const int32_t* table
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   int32_t* slot_of = static_cast<int32_t*>(workspace);
   int32_t* partial = slot_of + ((NB + 3) / 4) * 4;
-  const int64_t G = chunks_per_layer(RE, Q);
-  const int64_t chunk = (RE + G - 1) / G;
-  const long long LNB = (long long)n_layers * NB;
+  const int64_t G = chunks_per_layer(RE, n_layers);
+  int64_t chunk = (RE + G - 1) / G;
+  chunk = (chunk + 3) / 4 * 4;
+  int64_t rc_chunk = (NB + G - 1) / G;
+  rc_chunk = (rc_chunk + 3) / 4 * 4;
+  const bool vec = RE % 4 == 0 && aligned16(tables_in) && aligned16(tables_out);
+  const int rc_vec = NB % 4 == 0 && aligned16(refcount_in) && aligned16(refcount_out);
 
-  if (LNB > 0) {
-    remap_prepare_kernel<<<(unsigned)((LNB + 255) / 256), 256, 0, st>>>(slot_of, NB, refcount_in, refcount_out, LNB);
-    if (rc_status s = check_launch("rc_remap_block_table(prepare)")) return s;
-  }
   if (Q > 0 && NB > 0) {
     remap_scatter_kernel<<<(unsigned)((Q + 255) / 256), 256, 0, st>>>(slot_of, query_ids, (int)Q, NB);
     if (rc_status s = check_launch("rc_remap_block_table(scatter)")) return s;
   }
-  remap_gather_kernel<<<dim3((unsigned)G, (unsigned)n_layers), kGatherThreads, 0, st>>>(
-      tables_in, tables_out, RE, chunk, slot_of, pool_ids, match_idx, (int)Q, (int)P, NB, partial);
+  const dim3 grid((unsigned)G, (unsigned)n_layers);
+  const size_t hist_bytes = (size_t)(Q > 0 ? Q : 1) * sizeof(int);
+  if (vec)
+    remap_gather_kernel<true><<<grid, kGatherThreads, hist_bytes, st>>>(tables_in, tables_out, RE, chunk, slot_of, query_ids,
+                                                               pool_ids, match_idx, (int)Q, (int)P, NB, partial,
+                                                               refcount_in, refcount_out, rc_chunk, rc_vec);
+  else
+    remap_gather_kernel<false><<<grid, kGatherThreads, hist_bytes, st>>>(tables_in, tables_out, RE, chunk, slot_of, query_ids,
+                                                                pool_ids, match_idx, (int)Q, (int)P, NB, partial,
+                                                                refcount_in, refcount_out, rc_chunk, rc_vec);
   if (rc_status s = check_launch("rc_remap_block_table(gather)")) return s;
   remap_finalize_kernel<<<(unsigned)n_layers, kFinalThreads, 0, st>>>(partial, (int)G, query_ids, pool_ids, match_idx,
                                                                       (int)Q, (int)P, NB, refcount_out, freed,
