@@ -277,6 +277,51 @@ done:
 }
 
 /*
+ * Candidate-restricted scoring: Stage 2 as the paper runs it, only on the blocks of the steps
+ * that Stage 1 let through (Sec. IV-A: "For steps flagged as similar in Stage 1, this stage
+ * computes ... their corresponding KV cache blocks"; k candidates, k << m, in the complexity
+ * analysis).  cand[l][q][c] is a pool index or -1.  Each listed pair is scored from scratch
+ * with the same score as the exhaustive search; entries that are -1, out of range or dead
+ * score -inf.  best = highest score, ties to the lowest pool index; match iff best >= tau.
+ */
+int rc_oracle_candidates(int dtype, int mode, int L, int T, int H, int Dh,
+                         const uint16_t* kq, const uint16_t* vq, int64_t q_layer_stride, int64_t Q,
+                         const uint16_t* kp, const uint16_t* vp, int64_t p_layer_stride, int64_t P,
+                         const int32_t* cand, int64_t C, const uint8_t* live, double tau,
+                         double* scores, int32_t* best_idx, double* best_score, int32_t* match_idx) {
+  if (bad_shape(L, T, H, Dh, q_layer_stride, Q) || bad_shape(L, T, H, Dh, p_layer_stride, P) || C < 0) return 1;
+  if (!scores || !best_idx || !best_score || !match_idx || (C > 0 && !cand)) return 1;
+  const int64_t D = (int64_t)T * H * Dh;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t lq = 0; lq < (int64_t)L * Q; ++lq) {
+    const int64_t l = lq / Q, q = lq % Q;
+    double* buf = (double*)malloc(sizeof(double) * 4 * (size_t)D);
+    if (!buf) { err = 2; continue; }
+    decode_block(dtype, kq + l * q_layer_stride + q * D, D, buf);
+    decode_block(dtype, vq + l * q_layer_stride + q * D, D, buf + D);
+    int32_t bi = -1;
+    double bs = -INFINITY;
+    for (int64_t c = 0; c < C; ++c) {
+      const int32_t pidx = cand[(l * Q + q) * C + c];
+      double s = -INFINITY;
+      if (pidx >= 0 && pidx < P && (!live || live[l * P + pidx])) {
+        decode_block(dtype, kp + l * p_layer_stride + (int64_t)pidx * D, D, buf + 2 * D);
+        decode_block(dtype, vp + l * p_layer_stride + (int64_t)pidx * D, D, buf + 3 * D);
+        s = pair_score(buf, buf + D, buf + 2 * D, buf + 3 * D, T, H, Dh, mode);
+        if (s > bs || (s == bs && pidx < bi)) { bs = s; bi = pidx; }
+      }
+      scores[(l * Q + q) * C + c] = s;
+    }
+    best_idx[lq] = bi;
+    best_score[lq] = bs;
+    match_idx[lq] = (bi >= 0 && bs >= tau) ? bi : -1;
+    free(buf);
+  }
+  return err;
+}
+
+/*
  * Block-table remap with reference counts (Sec. IV-B), per layer:
  *   redirect = identity on [0, NB); redirect[query_ids[q]] = target(match_idx[q]) for matched q,
  *   target(m) = pool_ids ? pool_ids[m] : m;

@@ -147,6 +147,31 @@ def match(dtype, mode, kq, vq, kp, vp, live, tau, want_scores=False):
     return out
 
 
+def candidates(dtype, mode, kq, vq, kp, vp, cand, live, tau):
+    """Scores of the listed candidates [L][Q][C] (pool index or -1) and the best of each list."""
+    kq, vq, kp, vp = _kv(kq), _kv(vq), _kv(kp), _kv(vp)
+    L, Q, T, H, Dh = kq.shape
+    P = kp.shape[1]
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    assert cand.ndim == 3 and cand.shape[:2] == (L, Q)
+    C = cand.shape[2]
+    if live is not None:
+        live = np.ascontiguousarray(live, dtype=np.uint8)
+        assert live.shape == (L, P)
+    D = T * H * Dh
+    scores = np.zeros((L, Q, C), dtype=np.float64)
+    best_idx = np.zeros((L, Q), dtype=np.int32)
+    match_idx = np.zeros((L, Q), dtype=np.int32)
+    best_score = np.zeros((L, Q), dtype=np.float64)
+    rc = _load().rc_oracle_candidates(
+        ctypes.c_int(dtype), ctypes.c_int(mode), ctypes.c_int(L), ctypes.c_int(T), ctypes.c_int(H), ctypes.c_int(Dh),
+        _p(kq), _p(vq), ctypes.c_int64(Q * D), ctypes.c_int64(Q), _p(kp), _p(vp), ctypes.c_int64(P * D),
+        ctypes.c_int64(P), _p(cand), ctypes.c_int64(C), _p(live), ctypes.c_double(tau),
+        _p(scores), _p(best_idx), _p(best_score), _p(match_idx))
+    _check(rc, "candidates")
+    return dict(scores=scores, best_idx=best_idx, best_score=best_score, match_idx=match_idx)
+
+
 def remap(tables, query_ids, pool_ids, match_idx, P, NB, refcount):
     """Block-table remap.  Returns dict(tables, refcount, freed, n_remapped); inputs are not modified."""
     tables = np.ascontiguousarray(tables, dtype=np.int32)

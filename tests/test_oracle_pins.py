@@ -333,3 +333,43 @@ def test_remap_no_match_is_identity(oracle):
     r = oracle.remap(tables, qids, pids, match, P, NB, rc)
     assert np.array_equal(r["tables"], tables) and np.array_equal(r["refcount"], rc)
     assert not r["freed"].any() and not r["n_remapped"].any()
+
+
+# ---------------------------------------------------------------- candidate-restricted scoring
+@pytest.mark.parametrize("mode", [0, 1])
+def test_candidates_vs_exhaustive_and_brute_force(oracle, mode):
+    # The candidate scores must be the entries of the brute-force score matrix at the listed indices,
+    # and a list that names every live pool block must reproduce the exhaustive search.
+    rng = np.random.RandomState(40 + mode)
+    L, Q, P, T, H, Dh = 2, 4, 9, 2, 2, 4
+    D = T * H * Dh
+    kp, vp = rng.randn(L, P, D), rng.randn(L, P, D)
+    kq, vq = rng.randn(L, Q, D), rng.randn(L, Q, D)
+    kq[:, 0], vq[:, 0] = kp[:, 5], vp[:, 5]
+    kp[:, 7], vp[:, 7] = kp[:, 5], vp[:, 5]          # bit-identical pool blocks: lowest index wins
+    a = [enc(t, 0).reshape(L, -1, T, H, Dh) for t in (kq, vq, kp, vp)]
+    live = np.ones((L, P), dtype=np.uint8)
+    live[1, 5] = 0
+    S = brute_scores(*a, 0, mode)
+    cand = np.stack([np.stack([rng.permutation(P)[:4] for _ in range(Q)]) for _ in range(L)]).astype(np.int32)
+    cand[:, 0, :] = [7, 2, 5, -1]
+    cand[0, 1, 2] = P + 3                              # out of range: scores -inf
+    r = oracle.candidates(0, mode, *a, cand, live, 0.9)
+    for l in range(L):
+        for q in range(Q):
+            for c in range(4):
+                p = cand[l, q, c]
+                ok = 0 <= p < P and live[l, p]
+                if ok:
+                    assert r["scores"][l, q, c] == pytest.approx(S[l, q, p], abs=1e-12)
+                else:
+                    assert r["scores"][l, q, c] == -np.inf
+    assert r["best_idx"][0, 0] == 5 and r["match_idx"][0, 0] == 5 and r["best_score"][0, 0] == 1.0
+    assert r["best_idx"][1, 0] == 7                    # 5 is dead in layer 1
+    full = np.tile(np.arange(P, dtype=np.int32), (L, Q, 1))
+    rf = oracle.candidates(0, mode, *a, full, live, 0.9)
+    rm = oracle.match(0, mode, *a, live, 0.9)
+    assert np.array_equal(rf["best_idx"], rm["best_idx"]) and np.array_equal(rf["match_idx"], rm["match_idx"])
+    assert np.allclose(rf["best_score"], rm["best_score"], atol=1e-12)
+    empty = oracle.candidates(0, mode, *a, np.full((L, Q, 2), -1, np.int32), live, 0.9)
+    assert (empty["best_idx"] == -1).all() and np.isneginf(empty["best_score"]).all()
