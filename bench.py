@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="1..5, the workloads of the benchmark definition")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--candidates", type=int, default=16,
+                    help="C of the candidate-restricted scoring timed beside the step (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -159,6 +161,26 @@ def main():
             "hbm_frac": L * P * w.block_bytes / (pool_norm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "rc_remap_block_table": {"ms": remap_ms, "gb_per_s": remap_bytes / (remap_ms * 1e-3) / 1e9},
     }
+    if args.candidates > 0 and P > 0:
+        # candidate-restricted Stage 2 (not part of the step): C random pool blocks per query, timed the same way
+        C = args.candidates
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(12345)
+        cand = torch.randint(0, P, (L, Q, C), generator=gen, device=dev, dtype=torch.int32)
+        cout = rc.rc_score_candidates(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, pr["live"], cand, w.tau, w.mode)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            rc.rc_score_candidates(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, pr["live"], cand, w.tau,
+                                   w.mode, out=cout)
+        e1.record()
+        torch.cuda.synchronize()
+        cand_ms = e0.elapsed_time(e1) / args.steps
+        cand_bytes = L * Q * C * w.block_bytes       # one pool block per listed pair; the query block stays in the L2
+        kernels[f"rc_score_candidates(C={C}, not in the step)"] = {
+            "ms": cand_ms, "gb_per_s": cand_bytes / (cand_ms * 1e-3) / 1e9,
+            "hbm_frac": cand_bytes / (cand_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "pairs_per_s": L * Q * C / (cand_ms * 1e-3)}
     matched = int((out["match_idx"] >= 0).sum().item())
     n_remapped = int(res["n_remapped"].sum().item())
 

@@ -155,6 +155,31 @@ rc_status rc_remap_block_table(int32_t n_layers,
                                uint8_t* freed, int32_t* n_remapped,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Candidate-restricted scoring: Stage 2 in the shape the paper runs it (Sec. IV-A:
+ * only the blocks of the steps that Stage 1 flagged are compared; k candidates per
+ * step with k << m in the complexity analysis).  Every listed pair gets the same
+ * score as in rc_match_blocks; nothing else is read.  HBM bound: one pool block
+ * (2*T*H*Dh*2 bytes) per listed pair.
+ *
+ *   cand            DEVICE int32 [L][Q][C]: pool index, or -1 for an empty slot.  Entries
+ *                   outside [0, P) and dead blocks score -inf.
+ *   scores          DEVICE float [L][Q][C]
+ *   best_idx        DEVICE int32 [L][Q]: candidate with the highest score, equal scores to
+ *                   the lowest pool index; -1 if the list has no valid entry
+ *   best_score      DEVICE float [L][Q] (-inf if none);  match_idx: best_idx if >= tau else -1
+ * Everything else as in rc_match_blocks.  RC_SCORE_PER_HEAD_ALL needs n_kv_heads in
+ * {1, 2, 4, 8, 16}.  C == 0 writes -1 / -inf.
+ */
+rc_status rc_score_candidates(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_t mode,
+                              const void* kq, const void* vq, int64_t Q,
+                              const float* q_ksq, const float* q_vsq,
+                              const void* kp, const void* vp, int64_t P,
+                              const float* p_ksq, const float* p_vsq,
+                              const uint8_t* pool_live, const int32_t* cand, int64_t C, float tau,
+                              float* scores, int32_t* best_idx, float* best_score, int32_t* match_idx,
+                              void* hip_stream);
+
 /* HOST string describing the calling thread's last error ("" if none). Never NULL. */
 const char* rc_last_error(void);
 

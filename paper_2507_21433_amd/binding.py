@@ -17,7 +17,7 @@ RC_F16, RC_BF16 = 0, 1
 RC_SCORE_BLOCK, RC_SCORE_PER_HEAD_ALL = 0, 1
 
 EXPORTS = ("rc_block_norms", "rc_match_workspace_size", "rc_match_blocks", "rc_remap_workspace_size",
-           "rc_remap_block_table", "rc_last_error", "rc_version")
+           "rc_remap_block_table", "rc_score_candidates", "rc_last_error", "rc_version")
 
 
 class RcError(RuntimeError):
@@ -56,6 +56,9 @@ def lib():
         L.rc_remap_block_table.argtypes = [i32, vp, vp, i64, i64, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp,
                                            vp, sz, vp]
         L.rc_remap_block_table.restype = i32
+        L.rc_score_candidates.argtypes = [dp, dp, i32, vp, vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, vp, i64, f32,
+                                          vp, vp, vp, vp, vp]
+        L.rc_score_candidates.restype = i32
         L.rc_last_error.restype = ctypes.c_char_p
         L.rc_version.restype = i32
         _lib = L
@@ -174,3 +177,24 @@ def rc_remap_block_table(tables, query_ids, pool_ids, match_idx, P, NB, refcount
                                       _ptr(match_idx), Q, P, NB, _ptr(refcount), _ptr(r_out), _ptr(freed),
                                       _ptr(n_remapped), _ptr(workspace), workspace.numel(), _stream()))
     return dict(tables=t_out, refcount=r_out, freed=freed, n_remapped=n_remapped)
+
+
+def rc_score_candidates(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, pool_live, cand, tau, mode=RC_SCORE_BLOCK, out=None):
+    """Scores of the listed candidates [L][Q][C].  Returns dict(scores, best_idx, best_score, match_idx)."""
+    _dev(kq, vq, kp, vp, q_ksq, q_vsq, p_ksq, p_vsq, pool_live, cand)
+    qd, pd = kv_desc(kq), kv_desc(kp)
+    L, Q, P = kq.shape[0], kq.shape[1], kp.shape[1]
+    assert cand.dtype == torch.int32 and cand.dim() == 3 and cand.shape[:2] == (L, Q) and cand.is_contiguous()
+    C = cand.shape[2]
+    if pool_live is not None:
+        assert pool_live.dtype == torch.uint8 and pool_live.shape == (L, P) and pool_live.is_contiguous()
+    if out is None:
+        out = dict(scores=torch.empty((L, Q, C), dtype=torch.float32, device=kq.device),
+                   best_idx=torch.empty((L, Q), dtype=torch.int32, device=kq.device),
+                   best_score=torch.empty((L, Q), dtype=torch.float32, device=kq.device),
+                   match_idx=torch.empty((L, Q), dtype=torch.int32, device=kq.device))
+    _check(lib().rc_score_candidates(ctypes.byref(qd), ctypes.byref(pd), mode, _ptr(kq), _ptr(vq), Q, _ptr(q_ksq),
+                                     _ptr(q_vsq), _ptr(kp), _ptr(vp), P, _ptr(p_ksq), _ptr(p_vsq), _ptr(pool_live),
+                                     _ptr(cand), C, float(tau), _ptr(out["scores"]), _ptr(out["best_idx"]),
+                                     _ptr(out["best_score"]), _ptr(out["match_idx"]), _stream()))
+    return out

@@ -1,0 +1,194 @@
+// rc_score_candidates: Stage 2 restricted to listed candidates (ReasonCache Sec. IV-A: only the
+// blocks of the steps flagged by Stage 1 are compared).  HBM-bound gather: one workgroup per listed
+// pair streams the pool block's K and V tensors (the query block comes from the L2, which the other
+// candidates of the same query keep warm), accumulates the dot products in fp32 and normalises with
+// the cached squared norms.  A second small kernel picks the best candidate of every list.
+#include <hip/hip_runtime.h>
+
+#include "rc_common.hpp"
+
+namespace rc {
+namespace {
+
+constexpr int kCandThreads = 256;
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// <x, y> of the 8 fp16 / bf16 values packed in two 16-byte words, accumulated in fp32.
+template <bool BF16>
+__device__ __forceinline__ float dot8(u32x4 x, u32x4 y, float acc) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const unsigned int xi = x[i], yi = y[i];  // copies: a bit_cast applied to the vector element itself reads lane 0
+    if (BF16) {
+      acc = fmaf(__uint_as_float(xi << 16), __uint_as_float(yi << 16), acc);
+      acc = fmaf(__uint_as_float(xi & 0xffff0000u), __uint_as_float(yi & 0xffff0000u), acc);
+    } else {
+      acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, xi), __builtin_bit_cast(half2_t, yi), acc, false);
+    }
+  }
+  return acc;
+}
+
+struct CandParams {
+  const char *kq, *vq, *kp, *vp;
+  const float *q_ksq, *q_vsq, *p_ksq, *p_vsq;
+  const uint8_t* live;
+  const int32_t* cand;
+  float* scores;
+  long long q_lstride_b, p_lstride_b;
+  int Q, P, C;
+  int block_bytes;  // one K (or V) tensor of a block
+  int heads;        // 1 in block mode, H in per-head-all mode
+};
+
+// grid = (C, Q, L).  Thread t takes the 16-byte chunks t, t+256, ...; 16 consecutive chunks are one
+// head of one token, so with 16*heads dividing 256 a thread stays in one head: head = (t/16) % heads.
+template <bool BF16>
+__global__ __launch_bounds__(kCandThreads) void candidates_kernel(const CandParams p) {
+  __shared__ float part[2][kCandThreads / 16];
+  __shared__ float head_score[16];
+  const int c = blockIdx.x, q = blockIdx.y, tid = threadIdx.x;
+  const long long l = blockIdx.z;
+  const long long slot = (l * p.Q + q) * p.C + c;
+  const int pidx = p.cand[slot];
+  const bool valid = pidx >= 0 && pidx < p.P && (!p.live || p.live[l * p.P + pidx]);
+  if (!valid) {  // same for the whole workgroup
+    if (tid == 0) p.scores[slot] = -INFINITY;
+    return;
+  }
+  const u32x4* xq_k = reinterpret_cast<const u32x4*>(p.kq + l * p.q_lstride_b + (long long)q * p.block_bytes);
+  const u32x4* xq_v = reinterpret_cast<const u32x4*>(p.vq + l * p.q_lstride_b + (long long)q * p.block_bytes);
+  const u32x4* xp_k = reinterpret_cast<const u32x4*>(p.kp + l * p.p_lstride_b + (long long)pidx * p.block_bytes);
+  const u32x4* xp_v = reinterpret_cast<const u32x4*>(p.vp + l * p.p_lstride_b + (long long)pidx * p.block_bytes);
+  const int chunks = p.block_bytes / 16;
+  float dk = 0.f, dv = 0.f;
+#pragma unroll 4
+  for (int i = tid; i < chunks; i += kCandThreads) {  // chunks = 16*T*H is a multiple of 256
+    const u32x4 pk = __builtin_nontemporal_load(xp_k + i), pv = __builtin_nontemporal_load(xp_v + i);
+    dk = dot8<BF16>(xq_k[i], pk, dk);
+    dv = dot8<BF16>(xq_v[i], pv, dv);
+  }
+  // sum over the 16 lanes that share a (token, head) group, then over the groups of a head
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) {
+    dk += __shfl_xor(dk, off);
+    dv += __shfl_xor(dv, off);
+  }
+  if ((tid & 15) == 0) {
+    part[0][tid >> 4] = dk;
+    part[1][tid >> 4] = dv;
+  }
+  __syncthreads();
+  if (tid < p.heads) {
+    float sk = 0.f, sv = 0.f;
+    for (int g = tid; g < kCandThreads / 16; g += p.heads) {
+      sk += part[0][g];
+      sv += part[1][g];
+    }
+    const long long oq = (l * p.Q + q) * p.heads + tid, op = (l * p.P + pidx) * p.heads + tid;
+    const float nkq = p.q_ksq[oq], nvq = p.q_vsq[oq], nkp = p.p_ksq[op], nvp = p.p_vsq[op];
+    const float ck = (nkq > 0.f && nkp > 0.f) ? sk * __builtin_amdgcn_rsqf(nkq) * __builtin_amdgcn_rsqf(nkp) : 0.f;
+    const float cv = (nvq > 0.f && nvp > 0.f) ? sv * __builtin_amdgcn_rsqf(nvq) * __builtin_amdgcn_rsqf(nvp) : 0.f;
+    head_score[tid] = 0.5f * (ck + cv);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float s = head_score[0];
+    for (int h = 1; h < p.heads; ++h) s = fminf(s, head_score[h]);
+    p.scores[slot] = s;
+  }
+}
+
+// One thread per (layer, query): best of its list, equal scores to the lowest pool index.
+__global__ __launch_bounds__(256) void candidates_select_kernel(const float* __restrict__ scores,
+                                                                const int32_t* __restrict__ cand, long long LQ, int C,
+                                                                float tau, int32_t* __restrict__ best_idx,
+                                                                float* __restrict__ best_score,
+                                                                int32_t* __restrict__ match_idx) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= LQ) return;
+  float best = -INFINITY;
+  int bidx = -1;
+  for (int c = 0; c < C; ++c) {
+    const float s = scores[i * C + c];
+    const int pi = cand[i * C + c];
+    if (s == -INFINITY) continue;  // empty, out of range or dead
+    if (s > best || (s == best && pi < bidx) || bidx < 0) {
+      best = s;
+      bidx = pi;
+    }
+  }
+  best_idx[i] = bidx;
+  best_score[i] = best;
+  match_idx[i] = (bidx >= 0 && best >= tau) ? bidx : -1;
+}
+
+}  // namespace
+}  // namespace rc
+
+extern "C" rc_status rc_score_candidates(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_t mode,
+                                         const void* kq, const void* vq, int64_t Q, const float* q_ksq,
+                                         const float* q_vsq, const void* kp, const void* vp, int64_t P,
+                                         const float* p_ksq, const float* p_vsq, const uint8_t* pool_live,
+                                         const int32_t* cand, int64_t C, float tau, float* scores, int32_t* best_idx,
+                                         float* best_score, int32_t* match_idx, void* hip_stream) {
+  using namespace rc;
+  clear_error();
+  if (rc_status s = check_desc(qdesc, Q, "rc_score_candidates(query)")) return s;
+  if (rc_status s = check_desc(pdesc, P, "rc_score_candidates(pool)")) return s;
+  if (mode != RC_SCORE_BLOCK && mode != RC_SCORE_PER_HEAD_ALL)
+    return fail(RC_ERR_UNSUPPORTED, "rc_score_candidates: mode %d", mode);
+  if (qdesc->n_layers != pdesc->n_layers || qdesc->block_tokens != pdesc->block_tokens ||
+      qdesc->n_kv_heads != pdesc->n_kv_heads || qdesc->head_dim != pdesc->head_dim || qdesc->dtype != pdesc->dtype)
+    return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: query and pool descriptors differ in more than layer_stride");
+  if (C < 0) return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: negative C");
+  if (!(tau == tau)) return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: tau is NaN");
+  const int H = qdesc->n_kv_heads;
+  if (mode == RC_SCORE_PER_HEAD_ALL && (16 % H) != 0)
+    return fail(RC_ERR_UNSUPPORTED, "rc_score_candidates: per-head mode needs n_kv_heads in {1,2,4,8,16}, got %d", H);
+  const int L = qdesc->n_layers;
+  if (L == 0 || Q == 0) return RC_OK;
+  if (!kq || !vq || !q_ksq || !q_vsq || !best_idx || !best_score || !match_idx)
+    return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: NULL query or output pointer");
+  if (C > 0 && (!cand || !scores)) return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: NULL cand or scores");
+  if (C > 0 && P > 0 && (!kp || !vp || !p_ksq || !p_vsq))
+    return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: NULL pool pointer");
+  if (!aligned16(kq) || !aligned16(vq) || !aligned16(kp) || !aligned16(vp))
+    return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: KV pointer not 16-byte aligned");
+  if (C > 0x7fffffffLL || Q > 65535 || L > 65535 || P > 0x7fffffffLL)
+    return fail(RC_ERR_UNSUPPORTED, "rc_score_candidates: C, Q or L beyond the grid limits");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (C > 0) {
+    CandParams cp;
+    cp.kq = static_cast<const char*>(kq);
+    cp.vq = static_cast<const char*>(vq);
+    cp.kp = static_cast<const char*>(kp);
+    cp.vp = static_cast<const char*>(vp);
+    cp.q_ksq = q_ksq;
+    cp.q_vsq = q_vsq;
+    cp.p_ksq = p_ksq;
+    cp.p_vsq = p_vsq;
+    cp.live = pool_live;
+    cp.cand = cand;
+    cp.scores = scores;
+    cp.q_lstride_b = qdesc->layer_stride * 2;
+    cp.p_lstride_b = pdesc->layer_stride * 2;
+    cp.Q = (int)Q;
+    cp.P = (int)P;
+    cp.C = (int)C;
+    cp.block_bytes = qdesc->block_tokens * H * qdesc->head_dim * 2;  // T >= 16, Dh = 128: a multiple of 16 KB / 4
+    cp.heads = (mode == RC_SCORE_BLOCK) ? 1 : H;
+    const dim3 grid((unsigned)C, (unsigned)Q, (unsigned)L);
+    if (qdesc->dtype == RC_BF16)
+      candidates_kernel<true><<<grid, kCandThreads, 0, st>>>(cp);
+    else
+      candidates_kernel<false><<<grid, kCandThreads, 0, st>>>(cp);
+    if (rc_status s = check_launch("rc_score_candidates(score)")) return s;
+  }
+  const long long LQ = (long long)L * Q;
+  candidates_select_kernel<<<(unsigned)((LQ + 255) / 256), 256, 0, st>>>(scores, cand, LQ, (int)C, tau, best_idx,
+                                                                         best_score, match_idx);
+  return check_launch("rc_score_candidates(select)");
+}
