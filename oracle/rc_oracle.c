@@ -17,6 +17,8 @@
  *   - per-head-all mode: the same on each head's [T][Dh] slice, then min over heads;
  *   - best live pool block per query (lowest index on exact ties), runner-up
  *     value, match iff best >= tau (the Stage 2 sharing decision);
+ *   - the paper's own measure: layer-mean of (|Kq-Kp| + |Vq-Vp|)/(2dh), one decision per
+ *     block shared by all layers, match iff distance <= threshold;
  *   - block-table remap with reference counts (Sec. IV-B).
  *
  * Pins (tests/test_oracle_pins.py): bit decode against two library decoders,
@@ -24,7 +26,9 @@
  * the expansion, planted duplicates (score exactly 1), disjoint supports (score
  * exactly 0), K/V-averaging and per-head constructions with hand-known values,
  * the 1/sqrt(1+sigma^2) law for noisy copies, tie/dead/threshold cases, and for the
- * remap a hand-worked table plus conservation/idempotence invariants.
+ * remap a hand-worked table plus conservation/idempotence invariants; for the layer-mean
+ * distance a hand-worked 3-4-5 example, a library norm routine, metric properties and the
+ * expansion identity through the separately pinned norms and scores.
  * Every function here is pinned; none is "parity unpinned".
  */
 #include <math.h>
@@ -278,9 +282,8 @@ done:
 
 /*
  * Candidate-restricted scoring: Stage 2 as the paper runs it, only on the blocks of the steps
- * that Stage 1 let through (Sec. IV-A: "For steps flagged as similar in Stage 1, this stage
- * computes ... their corresponding KV cache blocks"; k candidates, k << m, in the complexity
- * analysis).  cand[l][q][c] is a pool index or -1.  Each listed pair is scored from scratch
+ * that Stage 1 let through (Sec. IV-A, opening of Stage 2; k candidates with k << m in the
+ * complexity analysis).  cand[l][q][c] is a pool index or -1.  Each listed pair is scored from scratch
  * with the same score as the exhaustive search; entries that are -1, out of range or dead
  * score -inf.  best = highest score, ties to the lowest pool index; match iff best >= tau.
  */
@@ -318,6 +321,79 @@ int rc_oracle_candidates(int dtype, int mode, int L, int T, int H, int Dh,
     match_idx[lq] = (bi >= 0 && bs >= tau) ? bi : -1;
     free(buf);
   }
+  return err;
+}
+
+/*
+ * Layer-mean block distance, the paper's own Stage 2 measure (Sec. IV-A, the two per-layer
+ * distance equations and the block-distance equation): for every layer the Euclidean distance
+ * of the flattened K tensors and of the flattened V tensors of the two blocks, each by
+ * subtracting and squaring; their sum divided by 2*d*h (d = T tokens per block, h = H KV
+ * heads); the mean of that over the N = L layers.  One decision per query block, shared by all
+ * layers: the nearest live pool block (lowest index on exact ties), the runner-up distance,
+ * match iff the distance is <= thr (so the largest collected distance used as the threshold
+ * accepts everything, the p = 100 row of the percentile table).  live is [P], shared by the layers.
+ * dist_out, if given, receives the whole [Q][P] matrix.
+ */
+int rc_oracle_layer_mean(int dtype, int L, int T, int H, int Dh,
+                         const uint16_t* kq, const uint16_t* vq, int64_t q_layer_stride, int64_t Q,
+                         const uint16_t* kp, const uint16_t* vp, int64_t p_layer_stride, int64_t P,
+                         const uint8_t* live, double thr,
+                         int32_t* best_idx, double* best_dist, int32_t* match_idx, double* second_dist,
+                         double* dist_out) {
+  if (L <= 0) return 1; /* a mean over no layers is undefined */
+  if (bad_shape(L, T, H, Dh, q_layer_stride, Q) || bad_shape(L, T, H, Dh, p_layer_stride, P)) return 1;
+  if (!best_idx || !best_dist || !match_idx || !second_dist) return 1;
+  if (Q > 0 && (!kq || !vq)) return 1;
+  if (P > 0 && (!kp || !vp)) return 1;
+  const int64_t D = (int64_t)T * H * Dh;
+  int err = 0;
+  double* qk = (double*)malloc(sizeof(double) * (size_t)(Q * D + 1));
+  double* qv = (double*)malloc(sizeof(double) * (size_t)(Q * D + 1));
+  double* S = (double*)calloc((size_t)(Q * P + 1), sizeof(double)); /* sum over layers */
+  if (!qk || !qv || !S) { err = 2; goto done; }
+  for (int l = 0; l < L; ++l) {
+    for (int64_t q = 0; q < Q; ++q) {
+      decode_block(dtype, kq + (int64_t)l * q_layer_stride + q * D, D, qk + q * D);
+      decode_block(dtype, vq + (int64_t)l * q_layer_stride + q * D, D, qv + q * D);
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t p = 0; p < P; ++p) {
+      double* pk = (double*)malloc(sizeof(double) * 2 * (size_t)D);
+      if (!pk) { err = 2; continue; }
+      double* pv = pk + D;
+      decode_block(dtype, kp + (int64_t)l * p_layer_stride + p * D, D, pk);
+      decode_block(dtype, vp + (int64_t)l * p_layer_stride + p * D, D, pv);
+      for (int64_t q = 0; q < Q; ++q) {
+        double sk = 0.0, sv = 0.0;
+        for (int64_t i = 0; i < D; ++i) {
+          const double a = qk[q * D + i] - pk[i], b = qv[q * D + i] - pv[i];
+          sk += a * a;
+          sv += b * b;
+        }
+        S[q * P + p] += (sqrt(sk) + sqrt(sv)) / (2.0 * T * H);
+      }
+      free(pk);
+    }
+    if (err) goto done;
+  }
+  for (int64_t q = 0; q < Q; ++q) {
+    int32_t bi = -1;
+    double bd = INFINITY, sd = INFINITY;
+    for (int64_t p = 0; p < P; ++p) {
+      const double d = S[q * P + p] / L;
+      if (dist_out) dist_out[q * P + p] = d;
+      if (live && !live[p]) continue;
+      if (d < bd) { sd = bd; bd = d; bi = (int32_t)p; }
+      else if (d < sd) sd = d;
+    }
+    best_idx[q] = bi;
+    best_dist[q] = bd;
+    second_dist[q] = sd;
+    match_idx[q] = (bi >= 0 && bd <= thr) ? bi : -1;
+  }
+done:
+  free(qk); free(qv); free(S);
   return err;
 }
 

@@ -172,6 +172,36 @@ def candidates(dtype, mode, kq, vq, kp, vp, cand, live, tau):
     return dict(scores=scores, best_idx=best_idx, best_score=best_score, match_idx=match_idx)
 
 
+def layer_mean(dtype, kq, vq, kp, vp, live, thr, want_dist=False):
+    """Layer-mean block distance and the per-block decision.  live is [P] or None.
+
+    Returns dict(best_idx, best_dist, match_idx, second_dist[, dist]) with [Q] arrays (dist is [Q][P])."""
+    kq, vq, kp, vp = _kv(kq), _kv(vq), _kv(kp), _kv(vp)
+    L, Q, T, H, Dh = kq.shape
+    P = kp.shape[1]
+    assert vq.shape == kq.shape and vp.shape == kp.shape and kp.shape[0] == L and kp.shape[2:] == kq.shape[2:]
+    if live is not None:
+        live = np.ascontiguousarray(live, dtype=np.uint8)
+        assert live.shape == (P,)
+    D = T * H * Dh
+    best_idx = np.zeros(Q, dtype=np.int32)
+    match_idx = np.zeros(Q, dtype=np.int32)
+    best = np.zeros(Q, dtype=np.float64)
+    second = np.zeros(Q, dtype=np.float64)
+    dist = np.zeros((Q, P), dtype=np.float64) if want_dist else None
+    rc = _load().rc_oracle_layer_mean(
+        ctypes.c_int(dtype), ctypes.c_int(L), ctypes.c_int(T), ctypes.c_int(H), ctypes.c_int(Dh),
+        _p(kq), _p(vq), ctypes.c_int64(Q * D), ctypes.c_int64(Q),
+        _p(kp), _p(vp), ctypes.c_int64(P * D), ctypes.c_int64(P),
+        _p(live), ctypes.c_double(thr),
+        _p(best_idx), _p(best), _p(match_idx), _p(second), _p(dist))
+    _check(rc, "layer_mean")
+    out = dict(best_idx=best_idx, best_dist=best, match_idx=match_idx, second_dist=second)
+    if want_dist:
+        out["dist"] = dist
+    return out
+
+
 def remap(tables, query_ids, pool_ids, match_idx, P, NB, refcount):
     """Block-table remap.  Returns dict(tables, refcount, freed, n_remapped); inputs are not modified."""
     tables = np.ascontiguousarray(tables, dtype=np.int32)

@@ -373,3 +373,128 @@ def test_candidates_vs_exhaustive_and_brute_force(oracle, mode):
     assert np.allclose(rf["best_score"], rm["best_score"], atol=1e-12)
     empty = oracle.candidates(0, mode, *a, np.full((L, Q, 2), -1, np.int32), live, 0.9)
     assert (empty["best_idx"] == -1).all() and np.isneginf(empty["best_score"]).all()
+
+
+# ---- the paper's own measure: layer-mean Euclidean block distance (Sec. IV-A Stage 2, block-distance equation)
+
+def layers(rows, T, H, Dh, dtype):
+    """[L][D] floats -> [L][1][T][H][Dh] bits (one block per layer)."""
+    return enc(np.asarray(rows, dtype=np.float32), dtype).reshape(len(rows), 1, T, H, Dh)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_layer_mean_golden(oracle, dtype):
+    cases = json.load(open(os.path.join(GOLD, "layer_mean_handworked.json")))["cases"]
+    for c in cases:
+        a = [layers(c[n], c["T"], c["H"], c["Dh"], dtype) for n in ("kq", "vq", "kp", "vp")]
+        r = oracle.layer_mean(dtype, *a, None, 1e9, want_dist=True)
+        assert r["dist"][0, 0] == pytest.approx(c["dist"], abs=1e-13), c["name"]
+        assert r["best_dist"][0] == pytest.approx(c["dist"], abs=1e-13) and r["best_idx"][0] == 0
+
+
+def rand_kv(rng, L, n, T, H, Dh, dtype):
+    return enc(rng.randn(L, n, T, H, Dh), dtype)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_layer_mean_vs_library_norm_and_expansion(oracle, dtype):
+    rng = np.random.RandomState(5)
+    L, Q, P, T, H, Dh = 3, 4, 7, 2, 3, 8
+    kq, vq, kp, vp = (rand_kv(rng, L, n, T, H, Dh, dtype) for n in (Q, Q, P, P))
+    r = oracle.layer_mean(dtype, kq, vq, kp, vp, None, 0.0, want_dist=True)
+    # (1) numpy's norm routine on library-decoded values
+    f = [dec(x, dtype).reshape(L, -1, T * H * Dh) for x in (kq, vq, kp, vp)]
+    want = np.zeros((Q, P))
+    for l in range(L):
+        for q in range(Q):
+            for p in range(P):
+                want[q, p] += (np.linalg.norm(f[0][l, q] - f[2][l, p]) + np.linalg.norm(f[1][l, q] - f[3][l, p])) / (2 * T * H)
+    want /= L
+    assert np.allclose(r["dist"], want, rtol=1e-13, atol=0)
+    # (2) the expansion of Stage 2 through the separately pinned norms and cosine scores:
+    #     with V := K the score is cos(Kq, Kp), so |x-y|^2 = |x|^2 + |y|^2 - 2 cos sqrt(|x|^2 |y|^2)
+    nq, _ = oracle.block_norms(dtype, oracle.BLOCK, kq, kq)
+    npk, _ = oracle.block_norms(dtype, oracle.BLOCK, kp, kp)
+    cosk = oracle.match(dtype, oracle.BLOCK, kq, kq, kp, kp, None, 0.0, want_scores=True)["scores"]
+    rk = oracle.layer_mean(dtype, kq, kq, kp, kp, None, 0.0, want_dist=True)["dist"]   # = mean_l 2 dK / (2dh)
+    dk = np.sqrt(nq[:, :, None] + npk[:, None, :] - 2 * cosk * np.sqrt(nq[:, :, None] * npk[:, None, :]))
+    assert np.allclose(rk, (2 * dk / (2 * T * H)).mean(axis=0), rtol=1e-11)
+    # (3) the direct single-pair routine
+    for (l, q, p) in [(0, 0, 0), (2, 3, 6)]:
+        one = oracle.layer_mean(dtype, kq[l:l + 1, q:q + 1], vq[l:l + 1, q:q + 1], kp[l:l + 1, p:p + 1], vp[l:l + 1, p:p + 1],
+                                None, 0.0, want_dist=True)["dist"][0, 0]
+        sk = oracle.sqdist(dtype, kq[l, q].ravel(), kp[l, p].ravel())
+        sv = oracle.sqdist(dtype, vq[l, q].ravel(), vp[l, p].ravel())
+        assert one == pytest.approx((np.sqrt(sk) + np.sqrt(sv)) / (2 * T * H), rel=1e-14)
+
+
+def test_layer_mean_metric_properties(oracle):
+    rng = np.random.RandomState(8)
+    L, n, T, H, Dh = 2, 5, 2, 2, 4
+    k, v = rand_kv(rng, L, n, T, H, Dh, 0), rand_kv(rng, L, n, T, H, Dh, 0)
+    d = oracle.layer_mean(0, k, v, k, v, None, 0.0, want_dist=True)["dist"]
+    assert (np.diag(d) == 0).all()                         # identity
+    assert np.array_equal(d, d.T)                          # symmetry (same products, same order)
+    for a in range(n):                                     # triangle inequality (sums of norms are norms of a product space)
+        for b in range(n):
+            for c in range(n):
+                assert d[a, c] <= d[a, b] + d[b, c] + 1e-12
+    # doubling every value (exact in fp16) doubles the distance
+    k2 = enc(2 * dec(k, 0), 0).reshape(k.shape)
+    v2 = enc(2 * dec(v, 0), 0).reshape(v.shape)
+    d2 = oracle.layer_mean(0, k2, v2, k2, v2, None, 0.0, want_dist=True)["dist"]
+    assert np.allclose(d2, 2 * d, rtol=1e-14)
+    # the mean over layers: identical layers give the single-layer value, the layer order is irrelevant,
+    # and the two-layer value is the average of the single-layer values
+    d0 = oracle.layer_mean(0, k[:1], v[:1], k[:1], v[:1], None, 0.0, want_dist=True)["dist"]
+    d1 = oracle.layer_mean(0, k[1:], v[1:], k[1:], v[1:], None, 0.0, want_dist=True)["dist"]
+    rep = oracle.layer_mean(0, np.repeat(k[:1], 3, 0), np.repeat(v[:1], 3, 0), np.repeat(k[:1], 3, 0), np.repeat(v[:1], 3, 0),
+                            None, 0.0, want_dist=True)["dist"]
+    assert np.allclose(rep, d0, rtol=1e-14)
+    assert np.allclose(d, 0.5 * (d0 + d1), rtol=1e-14)
+    flip = oracle.layer_mean(0, k[::-1], v[::-1], k[::-1], v[::-1], None, 0.0, want_dist=True)["dist"]
+    assert np.allclose(flip, d, rtol=1e-14)
+    # K and V enter symmetrically
+    sw = oracle.layer_mean(0, v, k, v, k, None, 0.0, want_dist=True)["dist"]
+    assert np.allclose(sw, d, rtol=1e-14)
+
+
+def test_layer_mean_selection_rules(oracle):
+    T, H, Dh = 1, 1, 4
+    mk = lambda rows: enc(np.asarray(rows, dtype=np.float32), 0).reshape(1, len(rows), T, H, Dh)
+    kq = mk([[0, 0, 0, 0], [10, 0, 0, 0]])
+    vq = mk([[0, 0, 0, 0], [0, 0, 0, 0]])
+    kp = mk([[4, 0, 0, 0], [0, 2, 0, 0], [0, 0, 2, 0], [0, 0, 0, 6], [10, 0, 0, 0]])
+    vp = mk([[0, 0, 0, 0]] * 5)
+    # query 0: distances 2, 1, 1, 3, 5 -> tie between pool 1 and 2 goes to 1, runner-up is the other 1
+    r = oracle.layer_mean(0, kq, vq, kp, vp, None, 1.0, want_dist=True)
+    assert np.allclose(r["dist"][0], [2, 1, 1, 3, 5])
+    assert r["best_idx"].tolist() == [1, 4] and r["best_dist"].tolist() == [1.0, 0.0]
+    assert r["second_dist"][0] == 1.0 and r["second_dist"][1] == 3.0   # query 1: |10 - 4| / 2
+    assert r["match_idx"].tolist() == [1, 4]               # distance == threshold still matches
+    assert oracle.layer_mean(0, kq, vq, kp, vp, None, 0.999)["match_idx"].tolist() == [-1, 4]
+    # dead blocks are skipped by the search, not rejected after it
+    live = np.array([1, 0, 1, 1, 0], dtype=np.uint8)
+    r = oracle.layer_mean(0, kq, vq, kp, vp, live, 1.0)
+    assert r["best_idx"].tolist() == [2, 0] and r["match_idx"].tolist() == [2, -1]
+    assert r["best_dist"][1] == 3.0 and r["second_dist"][0] == 2.0
+    # nothing live / empty pool
+    r = oracle.layer_mean(0, kq, vq, kp, vp, np.zeros(5, np.uint8), 1e9)
+    assert r["best_idx"].tolist() == [-1, -1] and np.isposinf(r["best_dist"]).all() and r["match_idx"].tolist() == [-1, -1]
+    r = oracle.layer_mean(0, kq, vq, kp[:, :0], vp[:, :0], None, 1e9)
+    assert r["best_idx"].tolist() == [-1, -1] and np.isposinf(r["second_dist"]).all()
+
+
+def test_layer_mean_noisy_copy_law(oracle):
+    # a copy with N(0, sigma^2) noise on every element sits at about 2 sigma sqrt(D) / (2dh) = sigma sqrt(Dh/(d h)) ... per tensor,
+    # i.e. d = sigma * sqrt(Dh / (T H)) for K plus V; fresh blocks at sqrt(2) times that with sigma = 1
+    w = synth.scaled(synth.WORKLOADS[1], L=2, P=24, Q=8, E=24, planted_frac=0.5, sigma=0.1)
+    pr = synth.make_problem(w, "cpu")
+    plan = pr["plan"]
+    r = oracle.layer_mean(0, *(synth.bits(pr[n]) for n in ("kq", "vq", "kp", "vp")), None, 0.5, want_dist=True)
+    unit = np.sqrt(w.Dh / (w.T * w.H))
+    d_planted = r["dist"][plan.planted_slots, plan.planted_targets]
+    assert np.allclose(d_planted, w.sigma * unit, rtol=0.03)
+    fresh = np.setdiff1d(np.arange(w.Q), plan.planted_slots)
+    assert np.allclose(r["dist"][fresh], np.sqrt(2) * unit, rtol=0.05)
+    assert (r["match_idx"][plan.planted_slots] == plan.planted_targets).all() and (r["match_idx"][fresh] == -1).all()
