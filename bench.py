@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="1..5, the workloads of the benchmark definition")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--layer-mean", type=int, default=1, help="also time the layer-mean distance entry point (0 = skip)")
     ap.add_argument("--candidates", type=int, default=16,
                     help="C of the candidate-restricted scoring timed beside the step (0 = skip)")
     args = ap.parse_args()
@@ -181,6 +182,23 @@ def main():
             "ms": cand_ms, "gb_per_s": cand_bytes / (cand_ms * 1e-3) / 1e9,
             "hbm_frac": cand_bytes / (cand_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "pairs_per_s": L * Q * C / (cand_ms * 1e-3)}
+    if args.layer_mean and P > 0 and w.mode == 0:
+        # the paper's own measure (not part of the step): layer-mean Euclidean distance, one decision per block
+        lv = pr["live"].min(dim=0).values.contiguous()
+        ws_lm = torch.empty(max(16, rc.rc_layer_mean_workspace_size(pr["kq"], Q, P)), dtype=torch.uint8, device=dev)
+        lm = rc.rc_match_blocks_layer_mean(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, lv, 0.5, workspace=ws_lm)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            rc.rc_match_blocks_layer_mean(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, lv, 0.5,
+                                          workspace=ws_lm, out=lm)
+        e1.record()
+        torch.cuda.synchronize()
+        lm_ms = e0.elapsed_time(e1) / args.steps
+        kernels["rc_match_blocks_layer_mean(not in the step)"] = {
+            "ms": lm_ms, "tflops": flop / (lm_ms * 1e-3) / 1e12, "mfma_frac": flop / (lm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype],
+            "kv_gb_per_s": kv_bytes / (lm_ms * 1e-3) / 1e9, "workspace_bytes": ws_lm.numel(),
+            "matched_blocks": int((lm["match_idx"] >= 0).sum().item())}
     matched = int((out["match_idx"] >= 0).sum().item())
     n_remapped = int(res["n_remapped"].sum().item())
 

@@ -180,6 +180,41 @@ rc_status rc_score_candidates(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, 
                               float* scores, int32_t* best_idx, float* best_score, int32_t* match_idx,
                               void* hip_stream);
 
+/* Bytes of DEVICE workspace rc_match_blocks_layer_mean needs (0 on bad arguments). */
+size_t rc_layer_mean_workspace_size(const rc_kv_desc* qdesc, int64_t Q, int64_t P);
+
+/*
+ * The paper's own Stage 2 measure and decision (Sec. IV-A, the per-layer K and V distance
+ * equations and the block-distance equation): per layer i the Euclidean distances
+ * dK_i = |K_i[q] - K_i[p]| and dV_i = |V_i[q] - V_i[p]| of the flattened tensors, through the
+ * expansion |x-y|^2 = |x|^2 + |y|^2 - 2 x.y with the cached squared norms, and
+ *
+ *     dist(q, p) = (1/L) * sum_i (dK_i + dV_i) / (2 * T * H).
+ *
+ * One decision per query block, shared by all layers (a layer-shared block table, as
+ * PagedAttention keeps it): the nearest live pool block, match iff dist <= threshold.
+ * Apply it with rc_remap_block_table(n_layers = 1, ...).
+ *
+ *   q_ksq .. p_vsq  DEVICE float [L][Q] / [L][P], squared norms of rc_block_norms in RC_SCORE_BLOCK mode
+ *   pool_live       DEVICE uint8 [P] (one flag per block, all layers), NULL = all live
+ *   threshold       on dist, e.g. the percentile rc_pat_threshold returns
+ *   best_idx        DEVICE int32 [Q]: argmin over live pool blocks, lowest index on exact ties, -1 if none
+ *   best_dist       DEVICE float [Q] (+inf if none);  match_idx: best_idx if best_dist <= threshold else -1
+ *   second_dist     DEVICE float [Q] or NULL: second-smallest distance, with multiplicity (+inf if fewer than two)
+ *   workspace       DEVICE, >= rc_layer_mean_workspace_size() bytes, 16-byte aligned, scratch
+ * fp32 throughout; a radicand that rounding pushes below 0 is clamped to 0.  n_layers must be
+ * >= 1 (RC_ERR_INVALID_ARG otherwise); Q == 0 launches nothing; P == 0 writes -1 / +inf.
+ */
+rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc,
+                                     const void* kq, const void* vq, int64_t Q,
+                                     const float* q_ksq, const float* q_vsq,
+                                     const void* kp, const void* vp, int64_t P,
+                                     const float* p_ksq, const float* p_vsq,
+                                     const uint8_t* pool_live, float threshold,
+                                     int32_t* best_idx, float* best_dist, int32_t* match_idx,
+                                     float* second_dist,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* HOST string describing the calling thread's last error ("" if none). Never NULL. */
 const char* rc_last_error(void);
 

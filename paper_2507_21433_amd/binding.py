@@ -17,7 +17,8 @@ RC_F16, RC_BF16 = 0, 1
 RC_SCORE_BLOCK, RC_SCORE_PER_HEAD_ALL = 0, 1
 
 EXPORTS = ("rc_block_norms", "rc_match_workspace_size", "rc_match_blocks", "rc_remap_workspace_size",
-           "rc_remap_block_table", "rc_score_candidates", "rc_last_error", "rc_version")
+           "rc_remap_block_table", "rc_score_candidates", "rc_layer_mean_workspace_size", "rc_match_blocks_layer_mean",
+           "rc_last_error", "rc_version")
 
 
 class RcError(RuntimeError):
@@ -59,6 +60,11 @@ def lib():
         L.rc_score_candidates.argtypes = [dp, dp, i32, vp, vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, vp, i64, f32,
                                           vp, vp, vp, vp, vp]
         L.rc_score_candidates.restype = i32
+        L.rc_layer_mean_workspace_size.argtypes = [dp, i64, i64]
+        L.rc_layer_mean_workspace_size.restype = sz
+        L.rc_match_blocks_layer_mean.argtypes = [dp, dp, vp, vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, f32,
+                                                 vp, vp, vp, vp, vp, sz, vp]
+        L.rc_match_blocks_layer_mean.restype = i32
         L.rc_last_error.restype = ctypes.c_char_p
         L.rc_version.restype = i32
         _lib = L
@@ -197,4 +203,36 @@ def rc_score_candidates(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, pool_live, c
                                      _ptr(q_vsq), _ptr(kp), _ptr(vp), P, _ptr(p_ksq), _ptr(p_vsq), _ptr(pool_live),
                                      _ptr(cand), C, float(tau), _ptr(out["scores"]), _ptr(out["best_idx"]),
                                      _ptr(out["best_score"]), _ptr(out["match_idx"]), _stream()))
+    return out
+
+
+def rc_layer_mean_workspace_size(kq, Q, P):
+    d = kv_desc(kq)
+    return lib().rc_layer_mean_workspace_size(ctypes.byref(d), Q, P)
+
+
+def rc_match_blocks_layer_mean(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, pool_live, threshold, want_second=True,
+                               workspace=None, out=None):
+    """Nearest live pool block per query by the layer-mean distance.  Returns dict(best_idx, best_dist, match_idx, second_dist), [Q]."""
+    _dev(kq, vq, kp, vp, q_ksq, q_vsq, p_ksq, p_vsq, pool_live)
+    qd, pd = kv_desc(kq), kv_desc(kp)
+    assert kv_desc(vq).layer_stride == qd.layer_stride and kv_desc(vp).layer_stride == pd.layer_stride
+    L, Q, P = kq.shape[0], kq.shape[1], kp.shape[1]
+    for t, n in ((q_ksq, Q), (q_vsq, Q), (p_ksq, P), (p_vsq, P)):
+        assert t.dtype == torch.float32 and t.is_contiguous() and t.shape == (L, n)
+    if pool_live is not None:
+        assert pool_live.dtype == torch.uint8 and pool_live.shape == (P,) and pool_live.is_contiguous()
+    need = lib().rc_layer_mean_workspace_size(ctypes.byref(qd), Q, P)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=kq.device)
+    if out is None:
+        out = dict(best_idx=torch.empty((Q,), dtype=torch.int32, device=kq.device),
+                   best_dist=torch.empty((Q,), dtype=torch.float32, device=kq.device),
+                   match_idx=torch.empty((Q,), dtype=torch.int32, device=kq.device),
+                   second_dist=torch.empty((Q,), dtype=torch.float32, device=kq.device) if want_second else None)
+    _check(lib().rc_match_blocks_layer_mean(ctypes.byref(qd), ctypes.byref(pd), _ptr(kq), _ptr(vq), Q, _ptr(q_ksq),
+                                            _ptr(q_vsq), _ptr(kp), _ptr(vp), P, _ptr(p_ksq), _ptr(p_vsq),
+                                            _ptr(pool_live), float(threshold), _ptr(out["best_idx"]),
+                                            _ptr(out["best_dist"]), _ptr(out["match_idx"]), _ptr(out.get("second_dist")),
+                                            _ptr(workspace), workspace.numel(), _stream()))
     return out

@@ -21,6 +21,8 @@
 // them, and the epilogue multiplies by aVq aVp / 2, with a = 1/sqrt(squared norm).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "rc_common.hpp"
 
 namespace rc {
@@ -51,12 +53,14 @@ struct MatchParams {
   const float *q_ksq, *q_vsq, *p_ksq, *p_vsq;
   const uint8_t* live;
   Part* part;                          // [L][npt][Q]
+  float* dpart;                        // layer-mean mode: [groups][P][Q] sums of layer distances
   long long q_lstride_b, p_lstride_b;  // bytes between layers
   int L, Q, P;
   int T, H;
   int npt, nqt;
-  int total;  // L * npt * nqt
+  int total;  // L * npt * nqt (layer-mean mode: groups * npt * nqt)
   int chunk;  // tiles handed to one XCD in a row
+  int G;      // layer-mean mode: layers per group (one workgroup walks the layers of its group)
 };
 
 __device__ __forceinline__ void top2_push(float v, int i, float& best, int& bidx, float& second) {
@@ -134,7 +138,9 @@ struct Cursor {
 
 }  // namespace
 
-// BP x BQ tile of one layer.  MODE 0 = block score, 1 = per-head-all.
+// BP x BQ tile of one layer.  MODE 0 = block score, 1 = per-head-all, 2 = layer-mean Euclidean
+// distance (the tile of a group of layers: the workgroup walks the layers one after the other and
+// adds |Kq-Kp| + |Vq-Vp| of every layer to the tile's running sum).
 template <bool BF16, int BP, int BQ, int MODE>
 __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
@@ -161,7 +167,10 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   if (tile >= p.total) return;
   const int qt = tile % p.nqt;
   const int pt = (tile / p.nqt) % p.npt;
-  const int l = tile / (p.nqt * p.npt);
+  const int lz = tile / (p.nqt * p.npt);  // layer, or group of layers in mode 2
+  const int l_first = (MODE == 2) ? lz * p.G : lz;
+  const int nl = (MODE == 2) ? min(p.G, p.L - l_first) : 1;
+  int l = l_first;
   const int p0 = pt * BP, q0 = qt * BQ;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -174,12 +183,16 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 
   // ---- buffer descriptors over this tile's rows of the four tensors.  The range check of the
   // buffer unit is a second guard; offsets are kept inside the rows anyway.
-  const long long offPool = l * p.p_lstride_b + (long long)p0 * row_b;
-  const long long offQry = l * p.q_lstride_b + (long long)q0 * row_b;
-  const i32x4 srdAk = make_srd(p.kp + offPool, (uint32_t)(rowsA * row_b));
-  const i32x4 srdAv = make_srd(p.vp + offPool, (uint32_t)(rowsA * row_b));
-  const i32x4 srdBk = make_srd(p.kq + offQry, (uint32_t)(rowsB * row_b));
-  const i32x4 srdBv = make_srd(p.vq + offQry, (uint32_t)(rowsB * row_b));
+  i32x4 srdAk, srdAv, srdBk, srdBv;
+  auto set_layer_tensors = [&]() {
+    const long long offPool = l * p.p_lstride_b + (long long)p0 * row_b;
+    const long long offQry = l * p.q_lstride_b + (long long)q0 * row_b;
+    srdAk = make_srd(p.kp + offPool, (uint32_t)(rowsA * row_b));
+    srdAv = make_srd(p.vp + offPool, (uint32_t)(rowsA * row_b));
+    srdBk = make_srd(p.kq + offQry, (uint32_t)(rowsB * row_b));
+    srdBv = make_srd(p.vq + offQry, (uint32_t)(rowsB * row_b));
+  };
+  set_layer_tensors();
 
   // ---- LDS layout of a stage: row r (one block) holds its 128-byte slice as eight 16-byte
   // chunks; logical chunk c sits at physical chunk c ^ (r & 7).  A fragment read (32 consecutive
@@ -203,9 +216,9 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // (MODE 1).  Step u of a phase reads 128 bytes per block at byte offset
   // head*256 + (u/2)*tok + (u%2)*128:  tok = 256 walks the flattened block, tok = H*256 walks
   // one head's [T][Dh] slice.
-  const int sps = (MODE == 0) ? (D / kBK) : (p.T * 2);
-  const int nphase = (MODE == 0) ? 2 : 2 * p.H;
-  const int tok = (MODE == 0) ? 256 : p.H * 256;
+  const int sps = (MODE != 1) ? (D / kBK) : (p.T * 2);
+  const int nphase = (MODE != 1) ? 2 : 2 * p.H;
+  const int tok = (MODE != 1) ? 256 : p.H * 256;
   auto advance = [&](Cursor& c) {
     if (++c.u == sps) {
       c.u = 0;
@@ -311,11 +324,15 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 
   // ---- scale factors, read from the cached squared norms when a phase ends.  Range-checked
   // buffer loads with 32-bit offsets: a row past the end of the pool / queries reads 0.
-  const int nh = (MODE == 0) ? 1 : p.H;
-  const __amdgpu_buffer_rsrc_t nQk = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q_ksq + (long long)l * p.Q * nh), 0, p.Q * nh * 4, 0x00020000);
-  const __amdgpu_buffer_rsrc_t nQv = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q_vsq + (long long)l * p.Q * nh), 0, p.Q * nh * 4, 0x00020000);
-  const __amdgpu_buffer_rsrc_t nPk = __builtin_amdgcn_make_buffer_rsrc((void*)(p.p_ksq + (long long)l * p.P * nh), 0, p.P * nh * 4, 0x00020000);
-  const __amdgpu_buffer_rsrc_t nPv = __builtin_amdgcn_make_buffer_rsrc((void*)(p.p_vsq + (long long)l * p.P * nh), 0, p.P * nh * 4, 0x00020000);
+  const int nh = (MODE != 1) ? 1 : p.H;
+  __amdgpu_buffer_rsrc_t nQk, nQv, nPk, nPv;
+  auto set_layer_norms = [&]() {
+    nQk = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q_ksq + (long long)l * p.Q * nh), 0, p.Q * nh * 4, 0x00020000);
+    nQv = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q_vsq + (long long)l * p.Q * nh), 0, p.Q * nh * 4, 0x00020000);
+    nPk = __builtin_amdgcn_make_buffer_rsrc((void*)(p.p_ksq + (long long)l * p.P * nh), 0, p.P * nh * 4, 0x00020000);
+    nPv = __builtin_amdgcn_make_buffer_rsrc((void*)(p.p_vsq + (long long)l * p.P * nh), 0, p.P * nh * 4, 0x00020000);
+  };
+  set_layer_norms();
   // Query column j of this lane: ratio rq = aK/aV and final factor fq = aV/2.
   auto query_scales = [&](int head, float (&rq)[TQ], float (&fq)[TQ]) {
 #pragma unroll
@@ -331,7 +348,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // Pool rows row .. row+3 of the tile: ratio rp = aK/aV and final factor fp = aV.
   auto pool_scales = [&](int row, int head, f32x4& rp, f32x4& fp) {
     f32x4 ksq, vsq;
-    if (MODE == 0) {
+    if (MODE != 1) {
       typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
       ksq = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nPk, (p0 + row) * 4, 0, 0));
       vsq = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nPv, (p0 + row) * 4, 0, 0));
@@ -373,7 +390,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   };
 
   // per-head mode: running minimum over heads of the finished head score; acc restarts at 0
-  f32x16 smin[MODE == 0 ? 1 : TP][MODE == 0 ? 1 : TQ];
+  f32x16 smin[MODE != 1 ? 1 : TP][MODE != 1 ? 1 : TQ];
   if (MODE == 1) {
 #pragma unroll
     for (int i = 0; i < TP; ++i)
@@ -396,12 +413,76 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float sc = acc[i][j][4 * g + e] * (fq[j] * fp[e]);
-            smin[MODE == 0 ? 0 : i][MODE == 0 ? 0 : j][4 * g + e] =
-                fminf(smin[MODE == 0 ? 0 : i][MODE == 0 ? 0 : j][4 * g + e], sc);
+            smin[MODE != 1 ? 0 : i][MODE != 1 ? 0 : j][4 * g + e] =
+                fminf(smin[MODE != 1 ? 0 : i][MODE != 1 ? 0 : j][4 * g + e], sc);
             acc[i][j][4 * g + e] = 0.f;
           }
         __builtin_amdgcn_sched_barrier(0);
       }
+  };
+
+  // layer-mean mode: when a phase (the K or the V tensor of one layer) ends, the accumulators hold
+  // the dot products; |x-y| = sqrt(|x|^2 + |y|^2 - 2 x.y) from the cached squared norms is added
+  // to the tile's running sum and the accumulators restart at 0.  Rounding can push the radicand
+  // of a near-duplicate pair slightly below 0: it is clamped.  The running sum has no room in the
+  // register file next to a 256x256 accumulator tile, so it lives in this workgroup's own part of
+  // the [group][P][Q] buffer (read-modify-write by the lane that owns the element, 0.5 MB per
+  // phase against 16 MB of operands); the first phase of a group only writes.  Range-checked
+  // buffer accesses: rows past the pool fall outside the descriptor, columns past the queries
+  // get an out-of-range offset.
+  auto fold = [&](const __amdgpu_buffer_rsrc_t& nQ, const __amdgpu_buffer_rsrc_t& nP, auto first_tag) {
+    constexpr bool first = decltype(first_tag)::value;
+    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+    int qs = p.Q * 4;  // bytes per row of the sums; opaque, so that the 256 offsets below are
+    asm volatile("" : "+s"(qs));  // formed here and not kept in registers across the layers
+    const __amdgpu_buffer_rsrc_t sums = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.dpart + ((long long)lz * p.P + p0) * p.Q), 0, rowsA * p.Q * 4, 0x00020000);
+    float nq[TQ];
+    int col[TQ];
+#pragma unroll
+    for (int j = 0; j < TQ; ++j) {
+      const int gq = q0 + wq * WTQ + j * 32 + (lane & 31);
+      nq[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nQ, gq * 4, 0, 0));
+      col[j] = gq < p.Q ? gq * 4 : -1;  // -1 = 0xffffffff: beyond any range
+    }
+    // one row tile (64 elements of the lane) at a time: all its loads are issued before the first
+    // store, so the lane pays one memory round trip per row tile and not one per element
+#pragma unroll
+    for (int i = 0; i < TP; ++i) {
+      float old[4][4][TQ];
+      f32x4 np[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int row = row_of(i, g);
+        np[g] = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nP, (p0 + row) * 4, 0, 0));
+        if (!first) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int j = 0; j < TQ; ++j) {
+              const int off = col[j] < 0 ? -1 : (row + e) * qs + col[j];
+              old[g][e][j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(sums, off, 0, 0));
+            }
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int row = row_of(i, g);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int j = 0; j < TQ; ++j) {
+            const int off = col[j] < 0 ? -1 : (row + e) * qs + col[j];
+            const float d2 = fmaf(-2.f, acc[i][j][4 * g + e], nq[j] + np[g][e]);
+            float d = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));
+            if (!first) d += old[g][e][j];
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, d), sums, off, 0, 0);
+            acc[i][j][4 * g + e] = 0.f;
+          }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
 
   // ---- main loop.  Per step: wait for this step's slices, barrier, then compute while refilling
@@ -409,16 +490,19 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // after).  The query loads are issued before the pool loads, so "at most LA loads outstanding"
   // means exactly: everything but the newest pool slice has landed.
   // prologue: query slice 0, pool slices 0 and 1; then the feeds point at query slice 1, pool slice 2
-  prepare(fb, srdBk, srdBv, ringB, B_STAGE);
+  auto prologue = [&]() {
+    prepare(fb, srdBk, srdBv, ringB, B_STAGE);
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dmaB(i);
-  next(fb, SB);
-  for (int k = 0; k < 2; ++k) {
-    prepare(fa, srdAk, srdAv, ringA, A_STAGE);
+    for (int i = 0; i < LB; ++i) dmaB(i);
+    next(fb, SB);
+    for (int k = 0; k < 2; ++k) {
+      prepare(fa, srdAk, srdAv, ringA, A_STAGE);
 #pragma unroll
-    for (int i = 0; i < LA; ++i) dmaA(i);
-    next(fa, SA);
-  }
+      for (int i = 0; i < LA; ++i) dmaA(i);
+      next(fa, SA);
+    }
+  };
+  prologue();
   int rdA = 0, rdB = 0;
   auto run_phase = [&]() {
     clear_pending();
@@ -439,15 +523,38 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     run_phase();
     rescale(0);
     run_phase();
-  } else {
+  } else if (MODE == 1) {
     for (int h = 0; h < p.H; ++h) {
       run_phase();
       rescale(h);
       run_phase();
       finish_head(h);
     }
+  } else {
+    for (int li = 0;;) {
+      run_phase();
+      if (li == 0)
+        fold(nQk, nPk, std::true_type{});
+      else
+        fold(nQk, nPk, std::false_type{});
+      run_phase();
+      fold(nQv, nPv, std::false_type{});
+      if (++li == nl) break;
+      // next layer of the group: the pipeline restarts from an empty ring
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();  // every wave has read its last fragments and its surplus refills have landed
+      l = l_first + li;
+      set_layer_tensors();
+      set_layer_norms();
+      fa = Feed{{0, 0}, 0, srdAk, 0, 0};
+      fb = Feed{{0, 0}, 0, srdBk, 0, 0};
+      rdA = rdB = 0;
+      prologue();
+    }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus refills of the last steps have landed
+
+  if (MODE == 2) return;  // the sums of this group's layers are in place: [group][pool row][query column]
 
   // ---- tile epilogue: scores, dead/tail masking, top-2 per query column
   float best[TQ], second[TQ];
@@ -481,7 +588,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
             if (MODE == 0)
               sc = acc[i][j][4 * g + e] * (fq[j] * fp[e]) + bias[e];
             else
-              sc = smin[MODE == 0 ? 0 : i][MODE == 0 ? 0 : j][4 * g + e] + bias[e];
+              sc = smin[MODE != 1 ? 0 : i][MODE != 1 ? 0 : j][4 * g + e] + bias[e];
             top2_push(sc, p0 + row + e, best[j], bidx[j], second[j]);
           }
         __builtin_amdgcn_sched_barrier(0);
@@ -544,6 +651,114 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(const Part* __restr
   if (second_score) second_score[i] = second;
 }
 
+// Layer-mean mode, selection: nearest live pool block per query from the [groups][P][Q] sums.
+// grid = (query tiles of 64, pool chunks of sel_rows rows); a thread owns one query column and
+// every fourth row of the chunk.  Works on -distance so that "higher wins, equal goes to the
+// lower index" is the same rule as for scores.
+__global__ __launch_bounds__(256) void layer_mean_select_kernel(const float* __restrict__ dpart, int groups, int P,
+                                                                int Q, int sel_rows, float scale,
+                                                                const uint8_t* __restrict__ live,
+                                                                Part* __restrict__ part) {
+  __shared__ Part s_part[4][64];
+  const int tq = threadIdx.x & 63, tp = threadIdx.x >> 6;
+  const int q = blockIdx.x * 64 + tq;
+  const int pbeg = blockIdx.y * sel_rows, pend = min(P, pbeg + sel_rows);
+  const long long gstride = (long long)P * Q;
+  float best = -INFINITY, second = -INFINITY;
+  int bidx = -1;
+  if (q < Q) {
+    for (int r = pbeg + tp; r < pend; r += 4) {
+      if (live && !live[r]) continue;
+      const float* src = dpart + (long long)r * Q + q;
+      float sum = 0.f;  // groups are added in ascending order: the same bits on every run
+      int g = 0;
+      for (; g + 8 <= groups; g += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + (g + u) * gstride);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += v[u];
+      }
+      for (; g < groups; ++g) sum += __builtin_nontemporal_load(src + g * gstride);
+      top2_push(-(sum * scale), r, best, bidx, second);
+    }
+  }
+  Part t;
+  t.best = best;
+  t.idx = bidx;
+  t.second = second;
+  t.pad = 0;
+  s_part[tp][tq] = t;
+  __syncthreads();
+  if (tp == 0 && q < Q) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const Part u = s_part[w][tq];
+      top2_merge(t.best, t.idx, t.second, u.best, u.idx, u.second);
+    }
+    part[(long long)blockIdx.y * Q + q] = t;
+  }
+}
+
+// rows of the pool per selection workgroup: about 2048 workgroups, at least 32 rows each
+inline int select_rows(int64_t P, int64_t Q) {
+  const int64_t qtiles = (Q + 63) / 64;
+  int64_t chunks = 2048 / (qtiles > 0 ? qtiles : 1);
+  if (chunks < 1) chunks = 1;
+  int64_t rows = (P + chunks - 1) / chunks;
+  rows = (rows + 31) / 32 * 32;
+  return (int)(rows < 32 ? 32 : rows);
+}
+
+// 64 queries per workgroup, four threads per query, each merging every fourth chunk.
+__global__ __launch_bounds__(256) void layer_mean_finalize_kernel(const Part* __restrict__ part, int nchunks, int Q,
+                                                                  float thr, int32_t* __restrict__ best_idx,
+                                                                  float* __restrict__ best_dist,
+                                                                  int32_t* __restrict__ match_idx,
+                                                                  float* __restrict__ second_dist) {
+  __shared__ Part s_part[4][64];
+  const int tq = threadIdx.x & 63, tc = threadIdx.x >> 6;
+  const int q = blockIdx.x * 64 + tq;
+  Part t;
+  t.best = -INFINITY;
+  t.second = -INFINITY;
+  t.idx = -1;
+  t.pad = 0;
+  if (q < Q)
+    for (int c = tc; c < nchunks; c += 4) {
+      const Part u = part[(long long)c * Q + q];
+      top2_merge(t.best, t.idx, t.second, u.best, u.idx, u.second);
+    }
+  s_part[tc][tq] = t;
+  __syncthreads();
+  if (tc != 0 || q >= Q) return;
+#pragma unroll
+  for (int w = 1; w < 4; ++w) {
+    const Part u = s_part[w][tq];
+    top2_merge(t.best, t.idx, t.second, u.best, u.idx, u.second);
+  }
+  best_idx[q] = t.idx;
+  best_dist[q] = -t.best;
+  match_idx[q] = (t.idx >= 0 && -t.best <= thr) ? t.idx : -1;
+  if (second_dist) second_dist[q] = -t.second;
+}
+
+// Layer-mean mode: how the L layers are split into groups.  A workgroup walks the layers of one
+// group, so large problems (many tiles) use one group and write every sum once; small ones split
+// the layers until there are enough workgroups to fill the chip.
+struct LayerSplit {
+  int G, groups;
+};
+inline LayerSplit layer_split(int L, int64_t tiles) {
+  int64_t want = (1024 + tiles - 1) / (tiles > 0 ? tiles : 1);
+  if (want < 1) want = 1;
+  if (want > L) want = L;
+  LayerSplit r;
+  r.G = (int)((L + want - 1) / want);
+  r.groups = (L + r.G - 1) / r.G;
+  return r;
+}
+
 // Tile shapes.  Block mode keeps a 128x128 accumulator tile per wave (all 256 accumulation
 // registers of a lane); per-head-all mode needs a second register tile for the running minimum
 // over heads and therefore uses half the rows.
@@ -554,6 +769,11 @@ constexpr TileShape kBlockTile = {256, 256};
 constexpr TileShape kHeadTile = {128, 256};
 
 inline TileShape tile_for(int mode) { return mode == RC_SCORE_BLOCK ? kBlockTile : kHeadTile; }
+
+// byte offset of the selection partials inside the layer-mean workspace (after the sums)
+inline size_t layer_mean_part_offset(int groups, int64_t P, int64_t Q) {
+  return (((size_t)groups * (size_t)P * (size_t)Q * sizeof(float)) + 255) & ~(size_t)255;
+}
 
 template <bool BF16>
 void launch_tiles(int mode, const MatchParams& mp, unsigned grid, hipStream_t st) {
@@ -633,6 +853,8 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.nqt = (int)nqt;
     mp.total = (int)total;
     mp.chunk = 32;
+    mp.dpart = nullptr;
+    mp.G = 1;
     const int64_t per_round = 8LL * mp.chunk;
     const unsigned grid = (unsigned)(((total + per_round - 1) / per_round) * per_round);
     if (qdesc->dtype == RC_BF16)
@@ -646,4 +868,95 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
                                                                      (int)Q, tau, best_idx, best_score, match_idx,
                                                                      second_score);
   return check_launch("rc_match_blocks(finalize)");
+}
+
+extern "C" size_t rc_layer_mean_workspace_size(const rc_kv_desc* qdesc, int64_t Q, int64_t P) {
+  using namespace rc;
+  if (!qdesc || Q < 0 || P < 0 || qdesc->n_layers <= 0) return 0;
+  const int64_t npt = (P + kBlockTile.bp - 1) / kBlockTile.bp, nqt = (Q + kBlockTile.bq - 1) / kBlockTile.bq;
+  const LayerSplit ls = layer_split(qdesc->n_layers, npt * nqt);
+  const int sel_rows = select_rows(P, Q);
+  const int64_t nchunks = (P + sel_rows - 1) / sel_rows;
+  return layer_mean_part_offset(ls.groups, P, Q) + (size_t)(nchunks > 0 ? nchunks : 1) * (size_t)(Q > 0 ? Q : 1) * sizeof(Part);
+}
+
+extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, const void* kq,
+                                                const void* vq, int64_t Q, const float* q_ksq, const float* q_vsq,
+                                                const void* kp, const void* vp, int64_t P, const float* p_ksq,
+                                                const float* p_vsq, const uint8_t* pool_live, float threshold,
+                                                int32_t* best_idx, float* best_dist, int32_t* match_idx,
+                                                float* second_dist, void* workspace, size_t workspace_bytes,
+                                                void* hip_stream) {
+  using namespace rc;
+  clear_error();
+  if (rc_status s = check_desc(qdesc, Q, "rc_match_blocks_layer_mean(query)")) return s;
+  if (rc_status s = check_desc(pdesc, P, "rc_match_blocks_layer_mean(pool)")) return s;
+  if (qdesc->n_layers != pdesc->n_layers || qdesc->block_tokens != pdesc->block_tokens ||
+      qdesc->n_kv_heads != pdesc->n_kv_heads || qdesc->head_dim != pdesc->head_dim || qdesc->dtype != pdesc->dtype)
+    return fail(RC_ERR_INVALID_ARG, "rc_match_blocks_layer_mean: query and pool descriptors differ in more than layer_stride");
+  if (!(threshold == threshold)) return fail(RC_ERR_INVALID_ARG, "rc_match_blocks_layer_mean: threshold is NaN");
+  const int L = qdesc->n_layers;
+  if (L <= 0) return fail(RC_ERR_INVALID_ARG, "rc_match_blocks_layer_mean: a mean over %d layers is undefined", L);
+  if (Q == 0) return RC_OK;
+  if (!kq || !vq || !q_ksq || !q_vsq || !best_idx || !best_dist || !match_idx)
+    return fail(RC_ERR_INVALID_ARG, "rc_match_blocks_layer_mean: NULL query or output pointer");
+  if (P > 0 && (!kp || !vp || !p_ksq || !p_vsq))
+    return fail(RC_ERR_INVALID_ARG, "rc_match_blocks_layer_mean: NULL pool pointer");
+  if (!aligned16(kq) || !aligned16(vq) || !aligned16(kp) || !aligned16(vp))
+    return fail(RC_ERR_INVALID_ARG, "rc_match_blocks_layer_mean: KV pointer not 16-byte aligned");
+  const TileShape ts = kBlockTile;
+  const int64_t npt = (P + ts.bp - 1) / ts.bp, nqt = (Q + ts.bq - 1) / ts.bq;
+  const LayerSplit ls = layer_split(L, npt * nqt);
+  const int64_t total = (int64_t)ls.groups * npt * nqt;
+  if (Q > 0x7fffffffLL || P > 0x7fffffffLL || total > 0x3fffffffLL || Q > (1LL << 20))
+    return fail(RC_ERR_UNSUPPORTED, "rc_match_blocks_layer_mean: problem beyond the grid limits");
+  const size_t need = rc_layer_mean_workspace_size(qdesc, Q, P);
+  if (!workspace || workspace_bytes < need || !aligned16(workspace))
+    return fail(RC_ERR_WORKSPACE, "rc_match_blocks_layer_mean: workspace of %zu bytes needed (16-byte aligned), got %zu",
+                need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* dpart = static_cast<float*>(workspace);
+  Part* part = reinterpret_cast<Part*>(static_cast<char*>(workspace) + layer_mean_part_offset(ls.groups, P, Q));
+  const int sel_rows = select_rows(P, Q);
+  const int64_t nchunks = (P + sel_rows - 1) / sel_rows;
+  if (P > 0) {
+    MatchParams mp;
+    mp.kq = static_cast<const char*>(kq);
+    mp.vq = static_cast<const char*>(vq);
+    mp.kp = static_cast<const char*>(kp);
+    mp.vp = static_cast<const char*>(vp);
+    mp.q_ksq = q_ksq;
+    mp.q_vsq = q_vsq;
+    mp.p_ksq = p_ksq;
+    mp.p_vsq = p_vsq;
+    mp.live = nullptr;  // eligibility is applied by the selection kernel
+    mp.part = nullptr;
+    mp.dpart = dpart;
+    mp.q_lstride_b = qdesc->layer_stride * 2;
+    mp.p_lstride_b = pdesc->layer_stride * 2;
+    mp.L = L;
+    mp.Q = (int)Q;
+    mp.P = (int)P;
+    mp.T = qdesc->block_tokens;
+    mp.H = qdesc->n_kv_heads;
+    mp.npt = (int)npt;
+    mp.nqt = (int)nqt;
+    mp.total = (int)total;
+    mp.chunk = 32;
+    mp.G = ls.G;
+    const int64_t per_round = 8LL * mp.chunk;
+    const unsigned grid = (unsigned)(((total + per_round - 1) / per_round) * per_round);
+    if (qdesc->dtype == RC_BF16)
+      match_tile_kernel<true, kBlockTile.bp, kBlockTile.bq, 2><<<grid, kThreads, 0, st>>>(mp);
+    else
+      match_tile_kernel<false, kBlockTile.bp, kBlockTile.bq, 2><<<grid, kThreads, 0, st>>>(mp);
+    if (rc_status s = check_launch("rc_match_blocks_layer_mean(tiles)")) return s;
+    const float scale = 1.0f / ((float)L * 2.0f * (float)qdesc->block_tokens * (float)qdesc->n_kv_heads);
+    const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)nchunks);
+    layer_mean_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, sel_rows, scale, pool_live, part);
+    if (rc_status s = check_launch("rc_match_blocks_layer_mean(select)")) return s;
+  }
+  layer_mean_finalize_kernel<<<(unsigned)((Q + 63) / 64), 256, 0, st>>>(part, (int)nchunks, (int)Q, threshold, best_idx,
+                                                                        best_dist, match_idx, second_dist);
+  return check_launch("rc_match_blocks_layer_mean(finalize)");
 }

@@ -59,3 +59,30 @@ def score_lookup(scores, idx):
     ll, qq = np.nonzero(ok)
     out[ll, qq] = scores[ll, qq, idx[ll, qq]]
     return out
+
+
+def dist_tol(T, H, Dh, rms=1.0):
+    """Tolerance on a layer-mean distance.
+
+    The GPU forms |x-y|^2 = |x|^2 + |y|^2 - 2 x.y in fp32; with a relative error eps on those three sums
+    (about 1e-6 observed, 6e-5 bound for chains of ~1000 additions) the radicand is off by eps*n*rms^2,
+    n = T*H*Dh, which for a near-duplicate pair costs sqrt(eps*n)*rms/(2*T*H) = sqrt(eps)/2 * rms*sqrt(Dh/(T*H)).
+    2e-3 of that unit (eps = 1.6e-5) is the bar; it is 2e-3 absolute for the benchmark shapes (Dh = T*H = 128)."""
+    return 2e-3 * rms * np.sqrt(Dh / (T * H))
+
+
+def check_layer_mean(gpu, orc, thr, dist_at_gpu_idx, tol):
+    """Layer-mean decision, [Q] arrays: the same rule as check_match on -distance (smaller distance = higher score)."""
+    g = dict(best_idx=gpu["best_idx"][None], best_score=-gpu["best_dist"][None], match_idx=gpu["match_idx"][None],
+             second_score=None if gpu.get("second_dist") is None else -gpu["second_dist"][None])
+    o = dict(best_idx=orc["best_idx"][None], best_score=-orc["best_dist"][None], match_idx=orc["match_idx"][None],
+             second_score=-orc["second_dist"][None])
+    return check_match(g, o, -thr, -dist_at_gpu_idx[None], tol)
+
+
+def dist_lookup(dist, idx):
+    """Oracle distance of (q, idx[q]) from a full [Q][P] matrix; NaN where idx < 0."""
+    out = np.full(idx.shape, np.nan)
+    ok = idx >= 0
+    out[ok] = dist[np.nonzero(ok)[0], idx[ok]]
+    return out
