@@ -19,6 +19,7 @@
  *     value, match iff best >= tau (the Stage 2 sharing decision);
  *   - the paper's own measure: layer-mean of (|Kq-Kp| + |Vq-Vp|)/(2dh), one decision per
  *     block shared by all layers, match iff distance <= threshold;
+ *   - the percentile threshold of the warm-up distances (nearest rank);
  *   - block-table remap with reference counts (Sec. IV-B).
  *
  * Pins (tests/test_oracle_pins.py): bit decode against two library decoders,
@@ -28,7 +29,8 @@
  * the 1/sqrt(1+sigma^2) law for noisy copies, tie/dead/threshold cases, and for the
  * remap a hand-worked table plus conservation/idempotence invariants; for the layer-mean
  * distance a hand-worked 3-4-5 example, a library norm routine, metric properties and the
- * expansion identity through the separately pinned norms and scores.
+ * expansion identity through the separately pinned norms and scores; for the percentile a
+ * library quantile routine, hand cases and the defining inequalities of a quantile.
  * Every function here is pinned; none is "parity unpinned".
  */
 #include <math.h>
@@ -395,6 +397,49 @@ int rc_oracle_layer_mean(int dtype, int L, int T, int H, int Dh,
 done:
   free(qk); free(qv); free(S);
   return err;
+}
+
+/*
+ * Percentile-based adaptive threshold (Sec. IV-A, "Percentile-based Adaptive Thresholding"; the
+ * parameter paragraph of the evaluation: the p % of the candidates with the lowest distances are
+ * kept).  From the distances collected during warm-up the threshold is the p-th percentile by
+ * the nearest-rank rule: with n finite samples sorted ascending, the k-th smallest,
+ * k = ceil(p/100 * n) clamped to [1, n] (in double).  It is a member of the sample, so the
+ * fraction of samples <= threshold is at least p %, and p = 100 gives the maximum (everything
+ * collected would have been accepted).  Non-finite samples (a query that had no candidate) are
+ * left out.  No finite sample: threshold = -inf (nothing is shared).
+ */
+static int cmp_float(const void* a, const void* b) {
+  const float x = *(const float*)a, y = *(const float*)b;
+  return (x > y) - (x < y);
+}
+
+int rc_oracle_pat_threshold(const float* samples, int64_t n, double p, float* threshold, int64_t* n_finite) {
+  if (n < 0 || (n > 0 && !samples) || !threshold || !n_finite || !(p >= 0.0 && p <= 100.0)) return 1;
+  float* s = (float*)malloc(sizeof(float) * (size_t)(n + 1));
+  if (!s) return 2;
+  int64_t m = 0;
+  for (int64_t i = 0; i < n; ++i)
+    if (isfinite(samples[i])) s[m++] = samples[i];
+  *n_finite = m;
+  if (m == 0) {
+    *threshold = -INFINITY;
+  } else {
+    qsort(s, (size_t)m, sizeof(float), cmp_float);
+    int64_t k = (int64_t)ceil(p * (double)m / 100.0);
+    if (k < 1) k = 1;
+    if (k > m) k = m;
+    *threshold = s[k - 1];
+  }
+  free(s);
+  return 0;
+}
+
+/* The sharing decision against a threshold that was computed, not given: match iff dist <= thr. */
+int rc_oracle_apply_threshold(const int32_t* best_idx, const float* best_dist, int64_t n, float thr, int32_t* match_idx) {
+  if (n < 0 || (n > 0 && (!best_idx || !best_dist || !match_idx))) return 1;
+  for (int64_t i = 0; i < n; ++i) match_idx[i] = (best_idx[i] >= 0 && best_dist[i] <= thr) ? best_idx[i] : -1;
+  return 0;
 }
 
 /*

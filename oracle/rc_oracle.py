@@ -202,6 +202,26 @@ def layer_mean(dtype, kq, vq, kp, vp, live, thr, want_dist=False):
     return out
 
 
+def pat_threshold(samples, p):
+    """Nearest-rank p-th percentile of the finite float32 samples.  Returns (threshold float32, n_finite)."""
+    samples = np.ascontiguousarray(samples, dtype=np.float32).ravel()
+    thr = np.zeros(1, dtype=np.float32)
+    cnt = np.zeros(1, dtype=np.int64)
+    rc = _load().rc_oracle_pat_threshold(_p(samples), ctypes.c_int64(samples.size), ctypes.c_double(p), _p(thr), _p(cnt))
+    _check(rc, "pat_threshold")
+    return thr[0], int(cnt[0])
+
+
+def apply_threshold(best_idx, best_dist, thr):
+    best_idx = np.ascontiguousarray(best_idx, dtype=np.int32).ravel()
+    best_dist = np.ascontiguousarray(best_dist, dtype=np.float32).ravel()
+    out = np.zeros(best_idx.size, dtype=np.int32)
+    rc = _load().rc_oracle_apply_threshold(_p(best_idx), _p(best_dist), ctypes.c_int64(best_idx.size),
+                                           ctypes.c_float(thr), _p(out))
+    _check(rc, "apply_threshold")
+    return out
+
+
 def remap(tables, query_ids, pool_ids, match_idx, P, NB, refcount):
     """Block-table remap.  Returns dict(tables, refcount, freed, n_remapped); inputs are not modified."""
     tables = np.ascontiguousarray(tables, dtype=np.int32)

@@ -498,3 +498,53 @@ def test_layer_mean_noisy_copy_law(oracle):
     fresh = np.setdiff1d(np.arange(w.Q), plan.planted_slots)
     assert np.allclose(r["dist"][fresh], np.sqrt(2) * unit, rtol=0.05)
     assert (r["match_idx"][plan.planted_slots] == plan.planted_targets).all() and (r["match_idx"][fresh] == -1).all()
+
+
+# ---- percentile-based adaptive threshold (Sec. IV-A, PAT; p = 80 in the evaluation's parameter paragraph)
+
+def test_pat_hand_cases(oracle):
+    s = np.array([5, 1, 4, 2, 3], dtype=np.float32)
+    # nearest rank on 5 samples: k = ceil(p/100 * 5)
+    for p, want in ((80, 4), (100, 5), (20, 1), (50, 3), (60, 3), (61, 4), (0, 1), (1, 1)):
+        thr, n = oracle.pat_threshold(s, p)
+        assert (thr, n) == (want, 5), p
+    # p = 100 accepts every collected distance, smaller p accepts at least p % of them
+    thr, _ = oracle.pat_threshold(s, 100)
+    assert (s <= thr).all()
+    # samples without a candidate (+inf), NaN and -inf are left out
+    thr, n = oracle.pat_threshold(np.array([np.inf, 2, np.nan, 1, -np.inf, 3], dtype=np.float32), 100)
+    assert (thr, n) == (3, 3)
+    thr, n = oracle.pat_threshold(np.array([np.inf, np.inf], dtype=np.float32), 80)
+    assert np.isneginf(thr) and n == 0
+    thr, n = oracle.pat_threshold(np.zeros(0, dtype=np.float32), 80)
+    assert np.isneginf(thr) and n == 0
+    # duplicates and a single sample
+    assert oracle.pat_threshold(np.array([2, 2, 2, 7], dtype=np.float32), 75)[0] == 2
+    assert oracle.pat_threshold(np.array([2, 2, 2, 7], dtype=np.float32), 76)[0] == 7
+    assert oracle.pat_threshold(np.array([9], dtype=np.float32), 0)[0] == 9
+
+
+def test_pat_vs_library_quantile_and_definition(oracle):
+    rng = np.random.RandomState(21)
+    for n in (1, 2, 7, 100, 1001, 4096):
+        s = np.abs(rng.randn(n)).astype(np.float32)
+        s[rng.rand(n) < 0.1] = s[0]                     # ties
+        for p in (0.0, 20.0, 50.0, 80.0, 99.9, 100.0, 33.3):
+            thr, cnt = oracle.pat_threshold(s, p)
+            assert cnt == n
+            # numpy's nearest-rank quantile (inverse of the empirical distribution function)
+            assert thr == np.percentile(s, p, method="inverted_cdf"), (n, p)
+            # the two inequalities that define a p-quantile of a sample
+            assert (s <= thr).sum() >= np.ceil(p / 100 * n - 1e-9)
+            assert (s < thr).sum() <= p / 100 * n + 1e-9
+    # order of the samples is irrelevant; negative values sort below positive ones
+    s = rng.randn(500).astype(np.float32)
+    assert oracle.pat_threshold(s, 80)[0] == oracle.pat_threshold(s[::-1], 80)[0] == np.sort(s)[399]
+
+
+def test_apply_threshold(oracle):
+    idx = np.array([3, -1, 5, 7, 2], dtype=np.int32)
+    d = np.array([0.5, np.inf, 0.25, 0.75, np.nan], dtype=np.float32)
+    assert oracle.apply_threshold(idx, d, np.float32(0.5)).tolist() == [3, -1, 5, -1, -1]   # inclusive; NaN never matches
+    assert oracle.apply_threshold(idx, d, np.float32(-np.inf)).tolist() == [-1] * 5          # warm-up: reuse disabled
+    assert oracle.apply_threshold(idx, d, np.float32(np.inf)).tolist() == [3, -1, 5, 7, -1]
