@@ -52,6 +52,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--layer-mean", type=int, default=1, help="also time the layer-mean distance entry point (0 = skip)")
+    ap.add_argument("--pat-samples", type=int, default=1 << 22, help="warm-up sample size for the percentile threshold (0 = skip)")
     ap.add_argument("--candidates", type=int, default=16,
                     help="C of the candidate-restricted scoring timed beside the step (0 = skip)")
     args = ap.parse_args()
@@ -199,6 +200,25 @@ def main():
             "ms": lm_ms, "tflops": flop / (lm_ms * 1e-3) / 1e12, "mfma_frac": flop / (lm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype],
             "kv_gb_per_s": kv_bytes / (lm_ms * 1e-3) / 1e9, "workspace_bytes": ws_lm.numel(),
             "matched_blocks": int((lm["match_idx"] >= 0).sum().item())}
+    if args.pat_samples > 0:
+        # percentile threshold over a warm-up sample of this many distances (not part of the step)
+        n = args.pat_samples
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(777)
+        smp = torch.where(torch.rand(n, generator=gen, device=dev) < 0.3,
+                          0.15 + 0.01 * torch.randn(n, generator=gen, device=dev),
+                          1.41 + 0.005 * torch.randn(n, generator=gen, device=dev)).contiguous()
+        ws_pat = torch.empty(rc.lib().rc_pat_workspace_size(), dtype=torch.uint8, device=dev)
+        po = rc.rc_pat_threshold(smp, 80.0, workspace=ws_pat)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            rc.rc_pat_threshold(smp, 80.0, workspace=ws_pat, out=po)
+        e1.record()
+        torch.cuda.synchronize()
+        pat_ms = e0.elapsed_time(e1) / args.steps
+        kernels[f"rc_pat_threshold(n={n}, p=80, not in the step)"] = {
+            "ms": pat_ms, "gb_per_s": 4.0 * n / (pat_ms * 1e-3) / 1e9, "threshold": float(po["threshold"].item())}
     matched = int((out["match_idx"] >= 0).sum().item())
     n_remapped = int(res["n_remapped"].sum().item())
 

@@ -215,6 +215,39 @@ rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const rc_kv_desc* 
                                      float* second_dist,
                                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Bytes of DEVICE workspace rc_pat_threshold needs (a constant, about 4 KB). */
+size_t rc_pat_workspace_size(void);
+
+/*
+ * Percentile-based adaptive threshold (Sec. IV-A, "Percentile-based Adaptive Thresholding";
+ * p = 80 in the evaluation's parameter paragraph: the p % of the candidates with the lowest
+ * distances are kept).  During warm-up the caller runs the search with sharing disabled
+ * (threshold -inf) and collects the distances; this call turns them into the threshold:
+ * the nearest-rank p-th percentile, i.e. with n_f finite samples the k-th smallest of them,
+ * k = ceil(p/100 * n_f) clamped to [1, n_f] (evaluated in double).  The result is a member of
+ * the sample and is exact (a radix select on the bit patterns, no interpolation); p = 100
+ * returns the largest collected distance.  Non-finite samples (queries that had no candidate)
+ * are left out; with no finite sample the threshold is -inf, which shares nothing.
+ *
+ *   samples         DEVICE float [n], n < 2^31, any order
+ *   p               percentile in [0, 100]
+ *   threshold       DEVICE float [1], written on the stream (no host synchronisation)
+ *   n_finite        DEVICE int64 [1] or NULL: number of samples that took part
+ *   workspace       DEVICE, >= rc_pat_workspace_size() bytes, 16-byte aligned, scratch
+ */
+rc_status rc_pat_threshold(const float* samples, int64_t n, float p,
+                           float* threshold, int64_t* n_finite,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The sharing decision against a threshold that lives in device memory (the output of
+ * rc_pat_threshold): match_idx[i] = best_idx[i] if best_idx[i] >= 0 and best_dist[i] <= *threshold,
+ * else -1 (Sec. IV-A: the percentile is the threshold "for all sharing decisions").
+ * All pointers DEVICE; n == 0 launches nothing.
+ */
+rc_status rc_apply_threshold(const int32_t* best_idx, const float* best_dist, int64_t n,
+                             const float* threshold, int32_t* match_idx, void* hip_stream);
+
 /* HOST string describing the calling thread's last error ("" if none). Never NULL. */
 const char* rc_last_error(void);
 

@@ -18,7 +18,7 @@ RC_SCORE_BLOCK, RC_SCORE_PER_HEAD_ALL = 0, 1
 
 EXPORTS = ("rc_block_norms", "rc_match_workspace_size", "rc_match_blocks", "rc_remap_workspace_size",
            "rc_remap_block_table", "rc_score_candidates", "rc_layer_mean_workspace_size", "rc_match_blocks_layer_mean",
-           "rc_last_error", "rc_version")
+           "rc_pat_workspace_size", "rc_pat_threshold", "rc_apply_threshold", "rc_last_error", "rc_version")
 
 
 class RcError(RuntimeError):
@@ -65,6 +65,12 @@ def lib():
         L.rc_match_blocks_layer_mean.argtypes = [dp, dp, vp, vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, f32,
                                                  vp, vp, vp, vp, vp, sz, vp]
         L.rc_match_blocks_layer_mean.restype = i32
+        L.rc_pat_workspace_size.argtypes = []
+        L.rc_pat_workspace_size.restype = sz
+        L.rc_pat_threshold.argtypes = [vp, i64, f32, vp, vp, vp, sz, vp]
+        L.rc_pat_threshold.restype = i32
+        L.rc_apply_threshold.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.rc_apply_threshold.restype = i32
         L.rc_last_error.restype = ctypes.c_char_p
         L.rc_version.restype = i32
         _lib = L
@@ -236,3 +242,30 @@ def rc_match_blocks_layer_mean(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, pool_
                                             _ptr(out["best_dist"]), _ptr(out["match_idx"]), _ptr(out.get("second_dist")),
                                             _ptr(workspace), workspace.numel(), _stream()))
     return out
+
+
+def rc_pat_threshold(samples, p, workspace=None, out=None):
+    """Nearest-rank p-th percentile of the finite samples.  Returns dict(threshold float32 [1], n_finite int64 [1]) on the device."""
+    _dev(samples)
+    assert samples.dtype == torch.float32 and samples.is_contiguous()
+    if workspace is None:
+        workspace = torch.empty(lib().rc_pat_workspace_size(), dtype=torch.uint8, device=samples.device)
+    if out is None:
+        out = dict(threshold=torch.empty(1, dtype=torch.float32, device=samples.device),
+                   n_finite=torch.empty(1, dtype=torch.int64, device=samples.device))
+    _check(lib().rc_pat_threshold(_ptr(samples), samples.numel(), float(p), _ptr(out["threshold"]), _ptr(out["n_finite"]),
+                                  _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def rc_apply_threshold(best_idx, best_dist, threshold, match_idx=None):
+    """match_idx = best_idx where best_dist <= threshold (a device scalar), else -1."""
+    _dev(best_idx, best_dist, threshold)
+    assert best_idx.dtype == torch.int32 and best_dist.dtype == torch.float32 and threshold.dtype == torch.float32
+    assert best_idx.is_contiguous() and best_dist.is_contiguous() and best_idx.shape == best_dist.shape
+    assert threshold.numel() == 1
+    if match_idx is None:
+        match_idx = torch.empty_like(best_idx)
+    _check(lib().rc_apply_threshold(_ptr(best_idx), _ptr(best_dist), best_idx.numel(), _ptr(threshold), _ptr(match_idx),
+                                    _stream()))
+    return match_idx
