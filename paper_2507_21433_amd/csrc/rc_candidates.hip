@@ -43,61 +43,90 @@ struct CandParams {
   int heads;        // 1 in block mode, H in per-head-all mode
 };
 
-// grid = (C, Q, L).  Thread t takes the 16-byte chunks t, t+256, ...; 16 consecutive chunks are one
-// head of one token, so with 16*heads dividing 256 a thread stays in one head: head = (t/16) % heads.
+// grid = (ceil(C / kCandPerWg), Q, L).  A workgroup scores kCandPerWg candidates of one query: the query
+// chunk a thread holds is used against all of them, which divides the query traffic from the L2.
+// Thread t takes the 16-byte chunks t, t+256, ...; 16 consecutive chunks are one head of one
+// token, so with 16*heads dividing 256 a thread stays in one head: head = (t/16) % heads.
+constexpr int kCandPerWg = 4;
+
 template <bool BF16>
 __global__ __launch_bounds__(kCandThreads) void candidates_kernel(const CandParams p) {
-  __shared__ float part[2][kCandThreads / 16];
-  __shared__ float head_score[16];
-  const int c = blockIdx.x, q = blockIdx.y, tid = threadIdx.x;
+  __shared__ float part[kCandPerWg][2][kCandThreads / 16];
+  __shared__ float head_score[kCandPerWg][16];
+  const int c0 = blockIdx.x * kCandPerWg, q = blockIdx.y, tid = threadIdx.x;
   const long long l = blockIdx.z;
-  const long long slot = (l * p.Q + q) * p.C + c;
-  const int pidx = p.cand[slot];
-  const bool valid = pidx >= 0 && pidx < p.P && (!p.live || p.live[l * p.P + pidx]);
-  if (!valid) {  // same for the whole workgroup
-    if (tid == 0) p.scores[slot] = -INFINITY;
-    return;
+  const long long slot0 = (l * p.Q + q) * p.C + c0;
+  int pidx[kCandPerWg];
+  bool valid[kCandPerWg];
+  const u32x4* xp_k[kCandPerWg];
+  const u32x4* xp_v[kCandPerWg];
+  bool any = false;
+#pragma unroll
+  for (int c = 0; c < kCandPerWg; ++c) {  // the same for the whole workgroup
+    pidx[c] = (c0 + c < p.C) ? p.cand[slot0 + c] : -1;
+    valid[c] = pidx[c] >= 0 && pidx[c] < p.P && (!p.live || p.live[l * p.P + pidx[c]]);
+    const long long off = l * p.p_lstride_b + (long long)(valid[c] ? pidx[c] : 0) * p.block_bytes;
+    xp_k[c] = reinterpret_cast<const u32x4*>(p.kp + off);
+    xp_v[c] = reinterpret_cast<const u32x4*>(p.vp + off);
+    any = any || valid[c];
+    if (!valid[c] && tid == 0 && c0 + c < p.C) p.scores[slot0 + c] = -INFINITY;
   }
+  if (!any) return;
   const u32x4* xq_k = reinterpret_cast<const u32x4*>(p.kq + l * p.q_lstride_b + (long long)q * p.block_bytes);
   const u32x4* xq_v = reinterpret_cast<const u32x4*>(p.vq + l * p.q_lstride_b + (long long)q * p.block_bytes);
-  const u32x4* xp_k = reinterpret_cast<const u32x4*>(p.kp + l * p.p_lstride_b + (long long)pidx * p.block_bytes);
-  const u32x4* xp_v = reinterpret_cast<const u32x4*>(p.vp + l * p.p_lstride_b + (long long)pidx * p.block_bytes);
   const int chunks = p.block_bytes / 16;
-  float dk = 0.f, dv = 0.f;
-#pragma unroll 4
+  float dk[kCandPerWg], dv[kCandPerWg];
+#pragma unroll
+  for (int c = 0; c < kCandPerWg; ++c) dk[c] = dv[c] = 0.f;
+#pragma unroll 2
   for (int i = tid; i < chunks; i += kCandThreads) {  // chunks = 16*T*H is a multiple of 256
-    const u32x4 pk = __builtin_nontemporal_load(xp_k + i), pv = __builtin_nontemporal_load(xp_v + i);
-    dk = dot8<BF16>(xq_k[i], pk, dk);
-    dv = dot8<BF16>(xq_v[i], pv, dv);
+    const u32x4 qk = xq_k[i], qv = xq_v[i];
+    u32x4 pk[kCandPerWg], pv[kCandPerWg];
+#pragma unroll
+    for (int c = 0; c < kCandPerWg; ++c)
+      if (valid[c]) {
+        pk[c] = __builtin_nontemporal_load(xp_k[c] + i);
+        pv[c] = __builtin_nontemporal_load(xp_v[c] + i);
+      }
+#pragma unroll
+    for (int c = 0; c < kCandPerWg; ++c)
+      if (valid[c]) {
+        dk[c] = dot8<BF16>(qk, pk[c], dk[c]);
+        dv[c] = dot8<BF16>(qv, pv[c], dv[c]);
+      }
   }
   // sum over the 16 lanes that share a (token, head) group, then over the groups of a head
 #pragma unroll
-  for (int off = 8; off > 0; off >>= 1) {
-    dk += __shfl_xor(dk, off);
-    dv += __shfl_xor(dv, off);
-  }
-  if ((tid & 15) == 0) {
-    part[0][tid >> 4] = dk;
-    part[1][tid >> 4] = dv;
+  for (int c = 0; c < kCandPerWg; ++c) {
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) {
+      dk[c] += __shfl_xor(dk[c], off);
+      dv[c] += __shfl_xor(dv[c], off);
+    }
+    if ((tid & 15) == 0) {
+      part[c][0][tid >> 4] = dk[c];
+      part[c][1][tid >> 4] = dv[c];
+    }
   }
   __syncthreads();
-  if (tid < p.heads) {
+  const int c = tid >> 4, h = tid & 15;  // one thread per (candidate, head)
+  if (c < kCandPerWg && h < p.heads && valid[c]) {
     float sk = 0.f, sv = 0.f;
-    for (int g = tid; g < kCandThreads / 16; g += p.heads) {
-      sk += part[0][g];
-      sv += part[1][g];
+    for (int g = h; g < kCandThreads / 16; g += p.heads) {
+      sk += part[c][0][g];
+      sv += part[c][1][g];
     }
-    const long long oq = (l * p.Q + q) * p.heads + tid, op = (l * p.P + pidx) * p.heads + tid;
+    const long long oq = (l * p.Q + q) * p.heads + h, op = (l * p.P + pidx[c]) * p.heads + h;
     const float nkq = p.q_ksq[oq], nvq = p.q_vsq[oq], nkp = p.p_ksq[op], nvp = p.p_vsq[op];
     const float ck = (nkq > 0.f && nkp > 0.f) ? sk * __builtin_amdgcn_rsqf(nkq) * __builtin_amdgcn_rsqf(nkp) : 0.f;
     const float cv = (nvq > 0.f && nvp > 0.f) ? sv * __builtin_amdgcn_rsqf(nvq) * __builtin_amdgcn_rsqf(nvp) : 0.f;
-    head_score[tid] = 0.5f * (ck + cv);
+    head_score[c][h] = 0.5f * (ck + cv);
   }
   __syncthreads();
-  if (tid == 0) {
-    float s = head_score[0];
-    for (int h = 1; h < p.heads; ++h) s = fminf(s, head_score[h]);
-    p.scores[slot] = s;
+  if (tid < kCandPerWg && valid[tid]) {
+    float s = head_score[tid][0];
+    for (int hh = 1; hh < p.heads; ++hh) s = fminf(s, head_score[tid][hh]);
+    p.scores[slot0 + tid] = s;
   }
 }
 
@@ -180,7 +209,7 @@ extern "C" rc_status rc_score_candidates(const rc_kv_desc* qdesc, const rc_kv_de
     cp.C = (int)C;
     cp.block_bytes = qdesc->block_tokens * H * qdesc->head_dim * 2;  // T >= 16, Dh = 128: a multiple of 16 KB / 4
     cp.heads = (mode == RC_SCORE_BLOCK) ? 1 : H;
-    const dim3 grid((unsigned)C, (unsigned)Q, (unsigned)L);
+    const dim3 grid((unsigned)((C + kCandPerWg - 1) / kCandPerWg), (unsigned)Q, (unsigned)L);
     if (qdesc->dtype == RC_BF16)
       candidates_kernel<true><<<grid, kCandThreads, 0, st>>>(cp);
     else
