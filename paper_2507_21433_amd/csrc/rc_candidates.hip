@@ -47,7 +47,7 @@ struct CandParams {
 // chunk a thread holds is used against all of them, which divides the query traffic from the L2.
 // Thread t takes the 16-byte chunks t, t+256, ...; 16 consecutive chunks are one head of one
 // token, so with 16*heads dividing 256 a thread stays in one head: head = (t/16) % heads.
-constexpr int kCandPerWg = 4;
+constexpr int kCandPerWg = 16;
 
 template <bool BF16>
 __global__ __launch_bounds__(kCandThreads) void candidates_kernel(const CandParams p) {
