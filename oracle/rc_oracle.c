@@ -20,6 +20,7 @@
  *   - the paper's own measure: layer-mean of (|Kq-Kp| + |Vq-Vp|)/(2dh), one decision per
  *     block shared by all layers, match iff distance <= threshold;
  *   - the percentile threshold of the warm-up distances (nearest rank);
+ *   - admission of unmatched query blocks into free pool slots, with their cached norms;
  *   - block-table remap with reference counts (Sec. IV-B).
  *
  * Pins (tests/test_oracle_pins.py): bit decode against two library decoders,
@@ -439,6 +440,51 @@ int rc_oracle_pat_threshold(const float* samples, int64_t n, double p, float* th
 int rc_oracle_apply_threshold(const int32_t* best_idx, const float* best_dist, int64_t n, float thr, int32_t* match_idx) {
   if (n < 0 || (n > 0 && (!best_idx || !best_dist || !match_idx))) return 1;
   for (int64_t i = 0; i < n; ++i) match_idx[i] = (best_idx[i] >= 0 && best_dist[i] <= thr) ? best_idx[i] : -1;
+  return 0;
+}
+
+/*
+ * Streaming pool maintenance (Sec. IV-B: the search runs inside every decoding step, so a block
+ * that found no partner stays resident and is itself a candidate from the next step on; Sec. IV-A:
+ * its squared norms are computed once and kept with the block).  Every unmatched query block
+ * (match_idx[q] < 0), in ascending q, takes the lowest-numbered slot of the pool that is not
+ * live: its K and V tensors of every layer and its cached squared norms are stored there and the
+ * slot becomes live.  When the free slots run out the remaining queries are left out
+ * (slot_of_query = -1).  Matched queries need no slot: their table entries already point at the
+ * partner.  nh = norm values per block (1, or H in per-head mode).  Everything is updated in place.
+ */
+int rc_oracle_pool_admit(int L, int64_t block_elems, int nh,
+                         const uint16_t* kq, const uint16_t* vq, int64_t q_layer_stride, int64_t Q,
+                         const double* q_ksq, const double* q_vsq,
+                         uint16_t* kp, uint16_t* vp, int64_t p_layer_stride, int64_t P,
+                         double* p_ksq, double* p_vsq, uint8_t* live, const int32_t* match_idx,
+                         int32_t* slot_of_query, int32_t* n_admitted) {
+  if (L < 0 || block_elems <= 0 || nh <= 0 || Q < 0 || P < 0 || !slot_of_query || !n_admitted) return 1;
+  if (Q > 0 && (!match_idx || (L > 0 && (!kq || !vq || !q_ksq || !q_vsq)))) return 1;
+  if (P > 0 && (!live || (L > 0 && (!kp || !vp || !p_ksq || !p_vsq)))) return 1;
+  int64_t next = 0; /* next pool slot to look at */
+  int32_t count = 0;
+  for (int64_t q = 0; q < Q; ++q) {
+    slot_of_query[q] = -1;
+    if (match_idx[q] >= 0) continue;
+    while (next < P && live[next]) ++next;
+    if (next >= P) continue; /* pool full */
+    const int64_t s = next;
+    for (int l = 0; l < L; ++l) {
+      memcpy(kp + (int64_t)l * p_layer_stride + s * block_elems, kq + (int64_t)l * q_layer_stride + q * block_elems,
+             sizeof(uint16_t) * (size_t)block_elems);
+      memcpy(vp + (int64_t)l * p_layer_stride + s * block_elems, vq + (int64_t)l * q_layer_stride + q * block_elems,
+             sizeof(uint16_t) * (size_t)block_elems);
+      for (int h = 0; h < nh; ++h) {
+        p_ksq[((int64_t)l * P + s) * nh + h] = q_ksq[((int64_t)l * Q + q) * nh + h];
+        p_vsq[((int64_t)l * P + s) * nh + h] = q_vsq[((int64_t)l * Q + q) * nh + h];
+      }
+    }
+    live[s] = 1;
+    slot_of_query[q] = (int32_t)s;
+    ++count;
+  }
+  *n_admitted = count;
   return 0;
 }
 

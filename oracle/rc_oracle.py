@@ -222,6 +222,32 @@ def apply_threshold(best_idx, best_dist, thr):
     return out
 
 
+def pool_admit(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, live, match_idx):
+    """Admit unmatched query blocks into free pool slots.  kp, vp, p_ksq, p_vsq, live are updated IN PLACE
+    (uint16 [L][P][T][H][Dh], float64 [L][P] or [L][P][H], uint8 [P]).  Returns (slot_of_query [Q], n_admitted)."""
+    kq, vq = _kv(kq), _kv(vq)
+    L, Q, T, H, Dh = kq.shape
+    P = kp.shape[1]
+    for a in (kp, vp):
+        assert a.dtype == np.uint16 and a.flags.c_contiguous and a.shape == (L, P, T, H, Dh)
+    nh = 1 if q_ksq.ndim == 2 else q_ksq.shape[2]
+    q_ksq, q_vsq = np.ascontiguousarray(q_ksq, dtype=np.float64), np.ascontiguousarray(q_vsq, dtype=np.float64)
+    for a in (p_ksq, p_vsq):
+        assert a.dtype == np.float64 and a.flags.c_contiguous and a.shape[:2] == (L, P)
+    assert live.dtype == np.uint8 and live.flags.c_contiguous and live.shape == (P,)
+    match_idx = np.ascontiguousarray(match_idx, dtype=np.int32)
+    assert match_idx.shape == (Q,)
+    slot = np.zeros(Q, dtype=np.int32)
+    n = np.zeros(1, dtype=np.int32)
+    D = T * H * Dh
+    rc = _load().rc_oracle_pool_admit(
+        ctypes.c_int(L), ctypes.c_int64(D), ctypes.c_int(nh), _p(kq), _p(vq), ctypes.c_int64(Q * D), ctypes.c_int64(Q),
+        _p(q_ksq), _p(q_vsq), _p(kp), _p(vp), ctypes.c_int64(P * D), ctypes.c_int64(P), _p(p_ksq), _p(p_vsq), _p(live),
+        _p(match_idx), _p(slot), _p(n))
+    _check(rc, "pool_admit")
+    return slot, int(n[0])
+
+
 def remap(tables, query_ids, pool_ids, match_idx, P, NB, refcount):
     """Block-table remap.  Returns dict(tables, refcount, freed, n_remapped); inputs are not modified."""
     tables = np.ascontiguousarray(tables, dtype=np.int32)

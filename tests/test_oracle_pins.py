@@ -548,3 +548,72 @@ def test_apply_threshold(oracle):
     assert oracle.apply_threshold(idx, d, np.float32(0.5)).tolist() == [3, -1, 5, -1, -1]   # inclusive; NaN never matches
     assert oracle.apply_threshold(idx, d, np.float32(-np.inf)).tolist() == [-1] * 5          # warm-up: reuse disabled
     assert oracle.apply_threshold(idx, d, np.float32(np.inf)).tolist() == [3, -1, 5, 7, -1]
+
+
+# ---- streaming pool maintenance (Sec. IV-B: the search is part of every decoding step)
+
+def test_pool_admit_hand_case(oracle):
+    T, H, Dh, L = 1, 1, 2, 2
+    kq = np.arange(100, 100 + L * 4 * 2, dtype=np.uint16).reshape(L, 4, T, H, Dh)
+    vq = kq + 50
+    kp = np.arange(L * 5 * 2, dtype=np.uint16).reshape(L, 5, T, H, Dh)
+    vp = kp + 20
+    kp0, vp0 = kp.copy(), vp.copy()
+    qn = np.arange(L * 4, dtype=np.float64).reshape(L, 4) + 0.5
+    pn = -np.ones((L, 5))
+    pk, pv = pn.copy(), pn.copy()
+    live = np.array([1, 0, 1, 0, 0], dtype=np.uint8)
+    slot, n = oracle.pool_admit(kq, vq, qn, qn + 100, kp, vp, pk, pv, live, np.array([-1, 3, -1, -1], dtype=np.int32))
+    # unmatched queries 0, 2, 3 take the dead slots 1, 3, 4 in that order; query 1 is matched and needs none
+    assert slot.tolist() == [1, -1, 3, 4] and n == 3 and live.tolist() == [1, 1, 1, 1, 1]
+    for q, s in ((0, 1), (2, 3), (3, 4)):
+        assert np.array_equal(kp[:, s], kq[:, q]) and np.array_equal(vp[:, s], vq[:, q])
+        assert np.array_equal(pk[:, s], qn[:, q]) and np.array_equal(pv[:, s], qn[:, q] + 100)
+    for s in (0, 2):                                   # live slots are untouched
+        assert np.array_equal(kp[:, s], kp0[:, s]) and np.array_equal(vp[:, s], vp0[:, s]) and (pk[:, s] == -1).all()
+
+
+def test_pool_admit_full_pool_and_noop(oracle):
+    rng = np.random.RandomState(12)
+    L, Q, P, T, H, Dh = 2, 6, 7, 1, 2, 4
+    kq, vq = (rng.randint(0, 60000, (L, Q, T, H, Dh)).astype(np.uint16) for _ in range(2))
+    kp, vp = (rng.randint(0, 60000, (L, P, T, H, Dh)).astype(np.uint16) for _ in range(2))
+    qk, qv = rng.rand(L, Q, H), rng.rand(L, Q, H)       # per-head norm layout
+    pk, pv = rng.rand(L, P, H), rng.rand(L, P, H)
+    live = np.array([1, 1, 0, 1, 1, 0, 1], dtype=np.uint8)
+    before = int(live.sum())
+    m = np.array([-1, -1, 2, -1, -1, -1], dtype=np.int32)
+    slot, n = oracle.pool_admit(kq, vq, qk, qv, kp, vp, pk, pv, live, m)
+    # two free slots for five unmatched queries: the first two in order get them, the rest are left out
+    assert slot.tolist() == [2, 5, -1, -1, -1, -1] and n == 2 and int(live.sum()) == before + n
+    assert np.array_equal(pk[:, 2], qk[:, 0]) and np.array_equal(pv[:, 5], qv[:, 1])
+    # a second call finds no room and changes nothing; so does a call in which every query matched
+    snap = [a.copy() for a in (kp, vp, pk, pv, live)]
+    slot, n = oracle.pool_admit(kq, vq, qk, qv, kp, vp, pk, pv, live, m)
+    assert n == 0 and (slot == -1).all() and all(np.array_equal(a, b) for a, b in zip(snap, (kp, vp, pk, pv, live)))
+    live[3] = 0
+    slot, n = oracle.pool_admit(kq, vq, qk, qv, kp, vp, pk, pv, live, np.zeros(Q, dtype=np.int32))
+    assert n == 0 and live[3] == 0
+
+
+def test_pool_admit_closes_the_loop(oracle):
+    # a block admitted in one step is found as an exact partner (distance 0, score 1) by its copy in the next step
+    w = synth.scaled(synth.WORKLOADS[1], L=2, P=12, Q=4, E=12, planted_frac=0.0)
+    pr = synth.make_problem(w, "cpu")
+    a = {n: synth.bits(pr[n]).copy() for n in ("kq", "vq", "kp", "vp")}
+    live = np.ones(w.P, dtype=np.uint8)
+    live[[5, 9]] = 0
+    qk, qv = oracle.block_norms(0, oracle.BLOCK, a["kq"], a["vq"])
+    pk, pv = oracle.block_norms(0, oracle.BLOCK, a["kp"], a["vp"])
+    first = oracle.layer_mean(0, a["kq"], a["vq"], a["kp"], a["vp"], live, 0.5)
+    assert (first["match_idx"] == -1).all()
+    slot, n = oracle.pool_admit(a["kq"], a["vq"], qk, qv, a["kp"], a["vp"], pk, pv, live, first["match_idx"])
+    assert slot.tolist() == [5, 9, -1, -1] and n == 2
+    # the cached norms that travelled with the blocks are the norms of what now sits in the slots
+    pk2, pv2 = oracle.block_norms(0, oracle.BLOCK, a["kp"], a["vp"])
+    assert np.array_equal(pk, pk2) and np.array_equal(pv, pv2)
+    again = oracle.layer_mean(0, a["kq"], a["vq"], a["kp"], a["vp"], live, 0.5)
+    assert again["best_idx"][:2].tolist() == [5, 9] and (again["best_dist"][:2] == 0).all()
+    assert again["match_idx"].tolist() == [5, 9, -1, -1]
+    s = oracle.match(0, oracle.BLOCK, a["kq"], a["vq"], a["kp"], a["vp"], np.tile(live, (w.L, 1)), 0.95)
+    assert (s["best_score"][:, :2] == 1.0).all() and (s["match_idx"][:, :2] == np.array([5, 9])).all()
