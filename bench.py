@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--layer-mean", type=int, default=1, help="also time the layer-mean distance entry point (0 = skip)")
     ap.add_argument("--pat-samples", type=int, default=1 << 22, help="warm-up sample size for the percentile threshold (0 = skip)")
+    ap.add_argument("--admit", type=int, default=1, help="also time the admission of unmatched blocks into the pool (0 = skip)")
     ap.add_argument("--candidates", type=int, default=16,
                     help="C of the candidate-restricted scoring timed beside the step (0 = skip)")
     args = ap.parse_args()
@@ -219,6 +220,30 @@ def main():
         pat_ms = e0.elapsed_time(e1) / args.steps
         kernels[f"rc_pat_threshold(n={n}, p=80, not in the step)"] = {
             "ms": pat_ms, "gb_per_s": 4.0 * n / (pat_ms * 1e-3) / 1e9, "threshold": float(po["threshold"].item())}
+    if args.admit and P >= 2 * Q and w.mode == 0:
+        # streaming pool maintenance (not part of the step): the last Q slots are declared free and every query of
+        # the step that no layer matched is admitted there (K, V and norms of all layers are copied)
+        live1 = pr["live"].min(dim=0).values.contiguous()
+        live1[P - Q:] = 0
+        none = (out["match_idx"] >= 0).sum(dim=0).eq(0)
+        m1 = torch.where(none, torch.full((Q,), -1, dtype=torch.int32, device=dev), torch.zeros(Q, dtype=torch.int32, device=dev))
+        live_w = live1.clone()
+        ws_ad = torch.empty(max(16, rc.lib().rc_pool_admit_workspace_size(Q, P)), dtype=torch.uint8, device=dev)
+        ao = rc.rc_pool_admit(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, live_w, m1, workspace=ws_ad)
+        torch.cuda.synchronize()
+        n_adm = int(ao["n_admitted"].item())
+        ad_ms = 0.0
+        for _ in range(args.steps):
+            live_w.copy_(live1)
+            e0.record()
+            rc.rc_pool_admit(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, live_w, m1, workspace=ws_ad, out=ao)
+            e1.record()
+            torch.cuda.synchronize()
+            ad_ms += e0.elapsed_time(e1) / args.steps
+        ad_bytes = 2.0 * n_adm * L * w.block_bytes        # every admitted block read once and written once
+        kernels["rc_pool_admit(not in the step)"] = {
+            "ms": ad_ms, "admitted_blocks": n_adm, "gb_per_s": ad_bytes / (ad_ms * 1e-3) / 1e9,
+            "hbm_frac": ad_bytes / (ad_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
     matched = int((out["match_idx"] >= 0).sum().item())
     n_remapped = int(res["n_remapped"].sum().item())
 

@@ -248,6 +248,37 @@ rc_status rc_pat_threshold(const float* samples, int64_t n, float p,
 rc_status rc_apply_threshold(const int32_t* best_idx, const float* best_dist, int64_t n,
                              const float* threshold, int32_t* match_idx, void* hip_stream);
 
+/* Bytes of DEVICE workspace rc_pool_admit needs (0 on bad arguments). */
+size_t rc_pool_admit_workspace_size(int64_t Q, int64_t P);
+
+/*
+ * Streaming pool maintenance (Sec. IV-B: the search is part of every decoding step, so a new
+ * block that found no partner stays resident and is itself a candidate from the next step on;
+ * Sec. IV-A: a block's squared norms are computed once and kept with the block).  Every
+ * unmatched query block (match_idx[q] < 0), in ascending q, takes the lowest-numbered pool slot
+ * that is not live: its K and V tensors of every layer and its squared norms are stored there
+ * and the slot becomes live.  When the free slots run out the remaining queries are left out.
+ * Matched queries need no slot.  The norm cache is dense (8 bytes per block and layer next to
+ * 64 KiB of KV), so no cached norm is ever evicted while its block is resident.
+ *
+ *   kq, vq, q_ksq, q_vsq   DEVICE, the step's query blocks and their norms (as for rc_match_blocks, `mode` gives
+ *                          the norm shape: [L][Q] or [L][Q][H])
+ *   kp, vp, p_ksq, p_vsq   DEVICE, the pool and its norm cache, updated in place; must not overlap the query buffers
+ *   pool_live              DEVICE uint8 [P], one flag per slot for all layers, updated in place
+ *   match_idx              DEVICE int32 [Q], the step's decisions (layer-shared, e.g. from rc_match_blocks_layer_mean)
+ *   slot_of_query          DEVICE int32 [Q]: the slot a query was admitted to, -1 if it matched or found no room
+ *   n_admitted             DEVICE int32 [1]
+ *   workspace              DEVICE, >= rc_pool_admit_workspace_size() bytes, 16-byte aligned, scratch
+ * No atomics: the same slots on every run.  Q == 0 or P == 0 admits nothing.
+ */
+rc_status rc_pool_admit(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_t mode,
+                        const void* kq, const void* vq, int64_t Q,
+                        const float* q_ksq, const float* q_vsq,
+                        void* kp, void* vp, int64_t P, float* p_ksq, float* p_vsq,
+                        uint8_t* pool_live, const int32_t* match_idx,
+                        int32_t* slot_of_query, int32_t* n_admitted,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* HOST string describing the calling thread's last error ("" if none). Never NULL. */
 const char* rc_last_error(void);
 

@@ -18,7 +18,8 @@ RC_SCORE_BLOCK, RC_SCORE_PER_HEAD_ALL = 0, 1
 
 EXPORTS = ("rc_block_norms", "rc_match_workspace_size", "rc_match_blocks", "rc_remap_workspace_size",
            "rc_remap_block_table", "rc_score_candidates", "rc_layer_mean_workspace_size", "rc_match_blocks_layer_mean",
-           "rc_pat_workspace_size", "rc_pat_threshold", "rc_apply_threshold", "rc_last_error", "rc_version")
+           "rc_pat_workspace_size", "rc_pat_threshold", "rc_apply_threshold", "rc_pool_admit_workspace_size", "rc_pool_admit",
+           "rc_last_error", "rc_version")
 
 
 class RcError(RuntimeError):
@@ -71,6 +72,10 @@ def lib():
         L.rc_pat_threshold.restype = i32
         L.rc_apply_threshold.argtypes = [vp, vp, i64, vp, vp, vp]
         L.rc_apply_threshold.restype = i32
+        L.rc_pool_admit_workspace_size.argtypes = [i64, i64]
+        L.rc_pool_admit_workspace_size.restype = sz
+        L.rc_pool_admit.argtypes = [dp, dp, i32, vp, vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rc_pool_admit.restype = i32
         L.rc_last_error.restype = ctypes.c_char_p
         L.rc_version.restype = i32
         _lib = L
@@ -269,3 +274,29 @@ def rc_apply_threshold(best_idx, best_dist, threshold, match_idx=None):
     _check(lib().rc_apply_threshold(_ptr(best_idx), _ptr(best_dist), best_idx.numel(), _ptr(threshold), _ptr(match_idx),
                                     _stream()))
     return match_idx
+
+
+def rc_pool_admit(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, pool_live, match_idx, mode=RC_SCORE_BLOCK, workspace=None,
+                  out=None):
+    """Admit unmatched query blocks into free pool slots; kp, vp, p_ksq, p_vsq, pool_live are updated in place.
+
+    Returns dict(slot_of_query int32 [Q], n_admitted int32 [1])."""
+    _dev(kq, vq, kp, vp, q_ksq, q_vsq, p_ksq, p_vsq, pool_live, match_idx)
+    qd, pd = kv_desc(kq), kv_desc(kp)
+    assert kv_desc(vq).layer_stride == qd.layer_stride and kv_desc(vp).layer_stride == pd.layer_stride
+    L, Q, P, H = kq.shape[0], kq.shape[1], kp.shape[1], kq.shape[3]
+    qs, ps = ((L, Q), (L, P)) if mode == RC_SCORE_BLOCK else ((L, Q, H), (L, P, H))
+    for t, sh in ((q_ksq, qs), (q_vsq, qs), (p_ksq, ps), (p_vsq, ps)):
+        assert t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == sh
+    assert pool_live.dtype == torch.uint8 and pool_live.shape == (P,) and pool_live.is_contiguous()
+    assert match_idx.dtype == torch.int32 and match_idx.shape == (Q,) and match_idx.is_contiguous()
+    if workspace is None:
+        workspace = torch.empty(max(16, lib().rc_pool_admit_workspace_size(Q, P)), dtype=torch.uint8, device=kq.device)
+    if out is None:
+        out = dict(slot_of_query=torch.empty((Q,), dtype=torch.int32, device=kq.device),
+                   n_admitted=torch.empty((1,), dtype=torch.int32, device=kq.device))
+    _check(lib().rc_pool_admit(ctypes.byref(qd), ctypes.byref(pd), mode, _ptr(kq), _ptr(vq), Q, _ptr(q_ksq), _ptr(q_vsq),
+                               _ptr(kp), _ptr(vp), P, _ptr(p_ksq), _ptr(p_vsq), _ptr(pool_live), _ptr(match_idx),
+                               _ptr(out["slot_of_query"]), _ptr(out["n_admitted"]), _ptr(workspace), workspace.numel(),
+                               _stream()))
+    return out
