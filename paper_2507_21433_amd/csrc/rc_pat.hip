@@ -45,22 +45,44 @@ __device__ __forceinline__ long long pat_rank(double p, long long n_f) {
   return k;
 }
 
-// The bytes fixed by passes 0 .. npass-1 (thread 0 only; s_h holds their histograms).
-__device__ __forceinline__ unsigned int pat_prefix(const unsigned int (*s_h)[256], int npass, long long k) {
+// Exclusive prefix sum of one value per thread over the 256 threads of the workgroup.
+__device__ __forceinline__ long long scan256(long long v, long long* s_wave /* [4] */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  long long incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const long long n = __shfl_up(incl, off);
+    if (lane >= off) incl += n;
+  }
+  __syncthreads();  // s_wave may still be read from the previous call
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  long long before = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) before += (w < wave) ? s_wave[w] : 0;
+  return before + incl - v;
+}
+
+// The bytes fixed by passes 0 .. npass-1 (s_h holds their histograms): in every pass the digit
+// whose bin contains rank k, found by all 256 threads together (thread d owns bin d).
+// Returns the prefix to every thread.  s_sel: two words of scratch.
+__device__ __forceinline__ unsigned int pat_prefix(const unsigned int (*s_h)[256], int npass, long long k,
+                                                   long long* s_wave, long long* s_sel) {
   unsigned int prefix = 0;
   for (int j = 0; j < npass; ++j) {
-    long long cum = 0;
-    int digit = 255;
-    for (int d = 0; d < 256; ++d) {
-      const long long c = s_h[j][d];
-      if (cum + c >= k) {
-        digit = d;
-        break;
-      }
-      cum += c;
+    const long long c = s_h[j][threadIdx.x];
+    const long long before = scan256(c, s_wave);
+    if (threadIdx.x == 0) s_sel[0] = -1;
+    __syncthreads();
+    if (c > 0 && before < k && k <= before + c) {  // exactly one bin, if k is within the total
+      s_sel[0] = threadIdx.x;
+      s_sel[1] = before;
     }
-    k -= cum;
+    __syncthreads();
+    const long long digit = s_sel[0] < 0 ? 255 : s_sel[0];
+    k -= s_sel[0] < 0 ? 0 : s_sel[1];
     prefix |= (unsigned int)digit << (24 - 8 * j);
+    __syncthreads();
   }
   return prefix;
 }
@@ -69,19 +91,15 @@ __global__ __launch_bounds__(kPatThreads) void pat_hist_kernel(const float* __re
                                                                PatState* st, int pass) {
   __shared__ unsigned int s_h[3][256];
   __shared__ unsigned int s_local[256];
-  __shared__ unsigned int s_prefix;
+  __shared__ long long s_wave[4], s_sel[2];
   __shared__ unsigned int s_bad;
   const int tid = threadIdx.x;
   s_local[tid] = 0u;
   if (tid == 0) s_bad = 0u;
   for (int j = 0; j < pass; ++j) s_h[j][tid] = st->hist[j][tid];
   __syncthreads();
-  if (tid == 0) {
-    const long long n_f = n - (long long)st->nonfinite;  // final once pass 0 is complete
-    s_prefix = (pass > 0 && n_f > 0) ? pat_prefix(s_h, pass, pat_rank(p, n_f)) : 0u;
-  }
-  __syncthreads();
-  const unsigned int prefix = s_prefix;
+  const long long n_f = n - (long long)st->nonfinite;  // final once pass 0 is complete
+  const unsigned int prefix = (pass > 0 && n_f > 0) ? pat_prefix(s_h, pass, pat_rank(p, n_f), s_wave, s_sel) : 0u;
   const unsigned int mask = pass == 0 ? 0u : 0xffffffffu << (32 - 8 * pass);
   const int shift = 24 - 8 * pass;
   unsigned int bad = 0;
@@ -100,12 +118,14 @@ __global__ __launch_bounds__(kPatThreads) void pat_final_kernel(long long n, dou
                                                                 float* __restrict__ threshold,
                                                                 long long* __restrict__ n_finite) {
   __shared__ unsigned int s_h[4][256];
+  __shared__ long long s_wave[4], s_sel[2];
   const int tid = threadIdx.x;
   for (int j = 0; j < 4; ++j) s_h[j][tid] = st->hist[j][tid];
   __syncthreads();
+  const long long n_f = n - (long long)st->nonfinite;
+  const unsigned int key = n_f > 0 ? pat_prefix(s_h, 4, pat_rank(p, n_f), s_wave, s_sel) : 0u;
   if (tid == 0) {
-    const long long n_f = n - (long long)st->nonfinite;
-    *threshold = n_f > 0 ? value_of(pat_prefix(s_h, 4, pat_rank(p, n_f))) : -INFINITY;
+    *threshold = n_f > 0 ? value_of(key) : -INFINITY;
     if (n_finite) *n_finite = n_f;
   }
 }
