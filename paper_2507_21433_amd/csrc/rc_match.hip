@@ -61,6 +61,8 @@ struct MatchParams {
   int total;  // L * npt * nqt (layer-mean mode: groups * npt * nqt)
   int chunk;  // tiles handed to one XCD in a row
   int G;      // layer-mean mode: layers per group (one workgroup walks the layers of its group)
+  int stagger_wgs;   // workgroups of the first round (one per compute unit) ...
+  int stagger_unit;  // ... start (tile % 16) * stagger_unit * 1024 clocks late
 };
 
 __device__ __forceinline__ void top2_push(float v, int i, float& best, int& bidx, float& second) {
@@ -172,6 +174,14 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   const int nl = (MODE == 2) ? min(p.G, p.L - l_first) : 1;
   int l = l_first;
   const int p0 = pt * BP, q0 = qt * BQ;
+
+  // With a single query tile, the pool tiles of a layer all read the same query slices.  Started
+  // together they ask the L2 for the same lines at the same moment, step after step; a start spread
+  // over a few steps keeps the requests apart, and the spread carries over to the later rounds.
+  // Nothing else changes.  (With several query tiles the tiles that share a pool slice must stay
+  // in step for the second one to find it in the L2: measured slower, so no spread there.)
+  if (wg < p.stagger_wgs && p.nqt == 1)
+    for (int i = 0; i < (pt & 15) * p.stagger_unit; ++i) __builtin_amdgcn_s_sleep(16);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -759,6 +769,22 @@ inline LayerSplit layer_split(int L, int64_t tiles) {
   return r;
 }
 
+// Compute units of the current device (a workgroup of the tile kernel fills one): the size of the
+// first round of workgroups.
+inline int compute_units() {
+  static thread_local int cached_dev = -1, cached_cus = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (dev != cached_dev) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    cached_dev = dev;
+    cached_cus = cus;
+  }
+  return cached_cus;
+}
+constexpr int kStaggerUnit = 6;  // x 1024 clocks per tile index, one to two pipeline steps (flat optimum between 3 and 8)
+
 // Tile shapes.  Block mode keeps a 128x128 accumulator tile per wave (all 256 accumulation
 // registers of a lane); per-head-all mode needs a second register tile for the running minimum
 // over heads and therefore uses half the rows.
@@ -855,6 +881,8 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.chunk = 32;
     mp.dpart = nullptr;
     mp.G = 1;
+    mp.stagger_wgs = compute_units();
+    mp.stagger_unit = kStaggerUnit;
     const int64_t per_round = 8LL * mp.chunk;
     const unsigned grid = (unsigned)(((total + per_round - 1) / per_round) * per_round);
     if (qdesc->dtype == RC_BF16)
@@ -944,6 +972,8 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     mp.total = (int)total;
     mp.chunk = 32;
     mp.G = ls.G;
+    mp.stagger_wgs = compute_units();
+    mp.stagger_unit = kStaggerUnit;
     const int64_t per_round = 8LL * mp.chunk;
     const unsigned grid = (unsigned)(((total + per_round - 1) / per_round) * per_round);
     if (qdesc->dtype == RC_BF16)
