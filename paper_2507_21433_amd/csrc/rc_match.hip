@@ -157,6 +157,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   static_assert(NT >= BQ, "one thread per query column in the tile epilogue");
   static_assert(RING <= 160 * 1024, "ring fits the LDS of a compute unit");
   static_assert(sizeof(Part) * WP * BQ <= RING, "the epilogue scratch reuses the ring");
+  static_assert(MODE != 2 || (BP == 256 && BQ == 256 && WP == 2 && WQ == 2), "sum_index() decodes this tile shape");
 
   __shared__ __attribute__((aligned(1024))) char s_ring[RING];
   const uint32_t ringA = lds_offset(s_ring), ringB = ringA + SA * A_STAGE;
@@ -435,62 +436,51 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // the dot products; |x-y| = sqrt(|x|^2 + |y|^2 - 2 x.y) from the cached squared norms is added
   // to the tile's running sum and the accumulators restart at 0.  Rounding can push the radicand
   // of a near-duplicate pair slightly below 0: it is clamped.  The running sum has no room in the
-  // register file next to a 256x256 accumulator tile, so it lives in this workgroup's own part of
-  // the [group][P][Q] buffer (read-modify-write by the lane that owns the element, 0.5 MB per
-  // phase against 16 MB of operands); the first phase of a group only writes.  Range-checked
-  // buffer accesses: rows past the pool fall outside the descriptor, columns past the queries
-  // get an out-of-range offset.
+  // register file next to a 256x256 accumulator tile, so it lives in this workgroup's own 256 KB
+  // of the sums buffer (read-modify-write by the lane that owns the element, 0.5 MB per phase
+  // against 16 MB of operands); the first phase of a group only writes.  The tile is stored in
+  // register order, not row-major: the four values a lane holds for (row tile i, register group
+  // g, column tile j) are one 16-byte word at index ((wave*TP + i)*4 + g)*TQ + j)*64 + lane, so
+  // every access of a wave is 1 KB contiguous (sum_index() below is the inverse map).
   auto fold = [&](const __amdgpu_buffer_rsrc_t& nQ, const __amdgpu_buffer_rsrc_t& nP, auto first_tag) {
     constexpr bool first = decltype(first_tag)::value;
     typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-    int qs = p.Q * 4;  // bytes per row of the sums; opaque, so that the 256 offsets below are
-    asm volatile("" : "+s"(qs));  // formed here and not kept in registers across the layers
-    const __amdgpu_buffer_rsrc_t sums = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(p.dpart + ((long long)lz * p.P + p0) * p.Q), 0, rowsA * p.Q * 4, 0x00020000);
+    long long tile_lin = ((long long)lz * p.npt + pt) * p.nqt + qt;
+    asm volatile("" : "+s"(tile_lin));  // opaque: the addresses are formed here, not kept across the layers
+    f32x4* sums = reinterpret_cast<f32x4*>(p.dpart) + tile_lin * (BP * BQ / 4) + (long long)wave * (TP * 4 * TQ * 64) + lane;
     float nq[TQ];
-    int col[TQ];
 #pragma unroll
-    for (int j = 0; j < TQ; ++j) {
-      const int gq = q0 + wq * WTQ + j * 32 + (lane & 31);
-      nq[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nQ, gq * 4, 0, 0));
-      col[j] = gq < p.Q ? gq * 4 : -1;  // -1 = 0xffffffff: beyond any range
-    }
+    for (int j = 0; j < TQ; ++j)
+      nq[j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nQ, (q0 + wq * WTQ + j * 32 + (lane & 31)) * 4, 0, 0));
     // one row tile (64 elements of the lane) at a time: all its loads are issued before the first
     // store, so the lane pays one memory round trip per row tile and not one per element
 #pragma unroll
     for (int i = 0; i < TP; ++i) {
-      float old[4][4][TQ];
+      f32x4 old[4][TQ];
       f32x4 np[4];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int row = row_of(i, g);
-        np[g] = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nP, (p0 + row) * 4, 0, 0));
+        np[g] = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nP, (p0 + row_of(i, g)) * 4, 0, 0));
         if (!first) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-#pragma unroll
-            for (int j = 0; j < TQ; ++j) {
-              const int off = col[j] < 0 ? -1 : (row + e) * qs + col[j];
-              old[g][e][j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(sums, off, 0, 0));
-            }
+          for (int j = 0; j < TQ; ++j) old[g][j] = sums[((i * 4 + g) * TQ + j) * 64];
         }
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int row = row_of(i, g);
+      for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
+        for (int j = 0; j < TQ; ++j) {
+          f32x4 d;
 #pragma unroll
-          for (int j = 0; j < TQ; ++j) {
-            const int off = col[j] < 0 ? -1 : (row + e) * qs + col[j];
+          for (int e = 0; e < 4; ++e) {
             const float d2 = fmaf(-2.f, acc[i][j][4 * g + e], nq[j] + np[g][e]);
-            float d = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));
-            if (!first) d += old[g][e][j];
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, d), sums, off, 0, 0);
+            d[e] = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));
+            if (!first) d[e] += old[g][j][e];
             acc[i][j][4 * g + e] = 0.f;
           }
-      }
+          sums[((i * 4 + g) * TQ + j) * 64] = d;
+        }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -564,7 +554,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus refills of the last steps have landed
 
-  if (MODE == 2) return;  // the sums of this group's layers are in place: [group][pool row][query column]
+  if (MODE == 2) return;  // the sums of this group's layers are in place, tile by tile in register order
 
   // ---- tile epilogue: scores, dead/tail masking, top-2 per query column
   float best[TQ], second[TQ];
@@ -661,36 +651,48 @@ __global__ __launch_bounds__(256) void match_finalize_kernel(const Part* __restr
   if (second_score) second_score[i] = second;
 }
 
-// Layer-mean mode, selection: nearest live pool block per query from the [groups][P][Q] sums.
-// grid = (query tiles of 64, pool chunks of sel_rows rows); a thread owns one query column and
-// every fourth row of the chunk.  Works on -distance so that "higher wins, equal goes to the
-// lower index" is the same rule as for scores.
+// Float index of element (row r, column c) of a 256x256 tile of sums as the tile kernel stores it
+// (2x2 waves of 128x128, four 32-row tiles x four 32-column tiles per wave, register group g holds
+// rows 8g + 4*(lane/32) + 0..3 of a row tile): r is a multiple of 4, the four rows r..r+3 follow.
+__device__ __forceinline__ int sum_index(int r, int c) {
+  const int wave = (r >> 7) * 2 + (c >> 7);
+  const int i = (r >> 5) & 3, g = (r >> 3) & 3, half = (r >> 2) & 1, j = (c >> 5) & 3;
+  const int lane = half * 32 + (c & 31);
+  return ((((wave * 4 + i) * 4 + g) * 4 + j) * 64 + lane) * 4;
+}
+
+// Layer-mean mode, selection: nearest live pool block per query from the sums (one 256x256 tile
+// after the other per group, each in the tile kernel's register order).
+// grid = (query tiles of 64, pool chunks of sel_rows rows, sel_rows a multiple of 16); a thread
+// owns one query column and every fourth group of four rows.  Works on -distance so that "higher
+// wins, equal goes to the lower index" is the same rule as for scores.
 __global__ __launch_bounds__(256) void layer_mean_select_kernel(const float* __restrict__ dpart, int groups, int P,
-                                                                int Q, int sel_rows, float scale,
+                                                                int Q, int npt, int nqt, int sel_rows, float scale,
                                                                 const uint8_t* __restrict__ live,
                                                                 Part* __restrict__ part) {
   __shared__ Part s_part[4][64];
   const int tq = threadIdx.x & 63, tp = threadIdx.x >> 6;
   const int q = blockIdx.x * 64 + tq;
   const int pbeg = blockIdx.y * sel_rows, pend = min(P, pbeg + sel_rows);
-  const long long gstride = (long long)P * Q;
+  const long long gstride = (long long)npt * nqt * 65536;
   float best = -INFINITY, second = -INFINITY;
   int bidx = -1;
   if (q < Q) {
-    for (int r = pbeg + tp; r < pend; r += 4) {
-      if (live && !live[r]) continue;
-      const float* src = dpart + (long long)r * Q + q;
-      float sum = 0.f;  // groups are added in ascending order: the same bits on every run
+    for (int r = pbeg + 4 * tp; r < pend; r += 16) {
+      const float* src = dpart + ((long long)(r >> 8) * nqt + (q >> 8)) * 65536 + sum_index(r & 255, q & 255);
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};  // groups are added in ascending order: the same bits on every run
       int g = 0;
-      for (; g + 8 <= groups; g += 8) {
-        float v[8];
+      for (; g + 4 <= groups; g += 4) {
+        f32x4 v[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + (g + u) * gstride);
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + (g + u) * gstride));
 #pragma unroll
-        for (int u = 0; u < 8; ++u) sum += v[u];
+        for (int u = 0; u < 4; ++u) sum += v[u];
       }
-      for (; g < groups; ++g) sum += __builtin_nontemporal_load(src + g * gstride);
-      top2_push(-(sum * scale), r, best, bidx, second);
+      for (; g < groups; ++g) sum += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + g * gstride));
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (r + e < pend && (!live || live[r + e])) top2_push(-(sum[e] * scale), r + e, best, bidx, second);
     }
   }
   Part t;
@@ -796,9 +798,10 @@ constexpr TileShape kHeadTile = {128, 256};
 
 inline TileShape tile_for(int mode) { return mode == RC_SCORE_BLOCK ? kBlockTile : kHeadTile; }
 
-// byte offset of the selection partials inside the layer-mean workspace (after the sums)
-inline size_t layer_mean_part_offset(int groups, int64_t P, int64_t Q) {
-  return (((size_t)groups * (size_t)P * (size_t)Q * sizeof(float)) + 255) & ~(size_t)255;
+// byte offset of the selection partials inside the layer-mean workspace (after the sums: one
+// 256x256 tile of floats per (group, pool tile, query tile))
+inline size_t layer_mean_part_offset(int groups, int64_t npt, int64_t nqt) {
+  return (size_t)groups * (size_t)npt * (size_t)nqt * 65536 * sizeof(float);
 }
 
 template <bool BF16>
@@ -905,7 +908,7 @@ extern "C" size_t rc_layer_mean_workspace_size(const rc_kv_desc* qdesc, int64_t 
   const LayerSplit ls = layer_split(qdesc->n_layers, npt * nqt);
   const int sel_rows = select_rows(P, Q);
   const int64_t nchunks = (P + sel_rows - 1) / sel_rows;
-  return layer_mean_part_offset(ls.groups, P, Q) + (size_t)(nchunks > 0 ? nchunks : 1) * (size_t)(Q > 0 ? Q : 1) * sizeof(Part);
+  return layer_mean_part_offset(ls.groups, npt, nqt) + (size_t)(nchunks > 0 ? nchunks : 1) * (size_t)(Q > 0 ? Q : 1) * sizeof(Part);
 }
 
 extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, const void* kq,
@@ -944,7 +947,7 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
                 need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   float* dpart = static_cast<float*>(workspace);
-  Part* part = reinterpret_cast<Part*>(static_cast<char*>(workspace) + layer_mean_part_offset(ls.groups, P, Q));
+  Part* part = reinterpret_cast<Part*>(static_cast<char*>(workspace) + layer_mean_part_offset(ls.groups, npt, nqt));
   const int sel_rows = select_rows(P, Q);
   const int64_t nchunks = (P + sel_rows - 1) / sel_rows;
   if (P > 0) {
@@ -983,7 +986,8 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     if (rc_status s = check_launch("rc_match_blocks_layer_mean(tiles)")) return s;
     const float scale = 1.0f / ((float)L * 2.0f * (float)qdesc->block_tokens * (float)qdesc->n_kv_heads);
     const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)nchunks);
-    layer_mean_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, sel_rows, scale, pool_live, part);
+    layer_mean_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, (int)npt, (int)nqt, sel_rows, scale,
+                                                    pool_live, part);
     if (rc_status s = check_launch("rc_match_blocks_layer_mean(select)")) return s;
   }
   layer_mean_finalize_kernel<<<(unsigned)((Q + 63) / 64), 256, 0, st>>>(part, (int)nchunks, (int)Q, threshold, best_idx,
