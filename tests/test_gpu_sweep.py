@@ -1,0 +1,91 @@
+"""Seeded sweep of random shapes inside the documented limits: every entry point against the CPU oracle on the same
+inputs.  Shapes straddle the 256 x 256 (and 128 x 256) tile edges, both dtypes, both modes, T in {16, 32}, H in 1..16.
+Needs a real MI355X."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_21433_amd import binding as rc
+from paper_2507_21433_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def draw(case):
+    r = np.random.RandomState(1000 + case)
+    edges = [1, 2, 31, 32, 33, 127, 128, 129, 255, 256, 257, 300, 511, 513, 600]
+    T = int(r.choice([16, 32]))
+    H = int(r.choice([1, 2, 3, 4, 5, 8, 12, 16]))
+    budget = 6e9 / (T * H * 128)                      # oracle work: L * P * Q * D kept near a second
+    P = int(r.choice(edges))
+    Q = int(r.choice([e for e in edges if e * P <= budget] or [1]))
+    L = int(max(1, min(4, budget // (P * Q))))
+    return dict(L=L, P=P, Q=Q, T=T, H=H, mode=int(r.randint(0, 2)), dtype=str(r.choice(["f16", "bf16"])),
+                planted_frac=float(r.choice([0.0, 0.3, 1.0])), seed=500 + case)
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shape(oracle, case):
+    kw = draw(case)
+    planted = min(int(kw["planted_frac"] * kw["Q"]), kw["P"])
+    kw["planted_frac"] = planted / kw["Q"]
+    w = synth.scaled(synth.WORKLOADS[2], name=f"sweep{case}", R=1, E=kw["P"] + kw["Q"], **kw)
+    say(f"{w.name}: L={w.L} P={w.P} Q={w.Q} T={w.T} H={w.H} mode={w.mode} {w.dtype} planted={planted}")
+    pr = synth.make_problem(w, DEV)
+    d = 0 if w.dtype == "f16" else 1
+    bits = [synth.bits(pr[n]) for n in ("kq", "vq", "kp", "vp")]
+    live = pr["live"]
+    # norms
+    qk, qv = rc.rc_block_norms(pr["kq"], pr["vq"], w.mode)
+    pk, pv = rc.rc_block_norms(pr["kp"], pr["vp"], w.mode)
+    ok, ov = oracle.block_norms(d, w.mode, bits[2], bits[3])
+    assert np.allclose(pk.cpu().numpy(), ok, rtol=2e-5, atol=0) and np.allclose(pv.cpu().numpy(), ov, rtol=2e-5, atol=0)
+    # exhaustive search
+    m = rc.rc_match_blocks(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, live, w.tau, w.mode)
+    torch.cuda.synchronize()
+    g = {k: v.cpu().numpy() for k, v in m.items()}
+    o = oracle.match(d, w.mode, *bits, live.cpu().numpy(), w.tau, want_scores=True)
+    rep = parity.check_match(g, o, w.tau, parity.score_lookup(o["scores"], g["best_idx"]))
+    # remap of the GPU's decisions
+    r = rc.rc_remap_block_table(pr["tables"], pr["query_ids"], None, m["match_idx"], w.P, w.NB, pr["refcount"])
+    torch.cuda.synchronize()
+    ro = oracle.remap(pr["tables"].cpu().numpy(), pr["query_ids"].cpu().numpy(), None, g["match_idx"], w.P, w.NB,
+                      pr["refcount"].cpu().numpy())
+    for k in ("tables", "refcount", "freed", "n_remapped"):
+        assert np.array_equal(r[k].cpu().numpy(), ro[k]), k
+    # candidate lists (per-head lists need a head count that divides 16)
+    if w.mode == 0 or 16 % w.H == 0:
+        rng = np.random.RandomState(case)
+        C = int(rng.randint(1, 20))
+        cand = rng.randint(-1, w.P, size=(w.L, w.Q, C)).astype(np.int32)
+        c = rc.rc_score_candidates(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, live,
+                                   torch.as_tensor(cand, device=DEV), w.tau, w.mode)
+        torch.cuda.synchronize()
+        co = oracle.candidates(d, w.mode, *bits, cand, live.cpu().numpy(), w.tau)
+        cs = c["scores"].cpu().numpy().astype(np.float64)
+        fin = np.isfinite(co["scores"])
+        assert np.array_equal(np.isfinite(cs), fin)
+        assert not fin.any() or np.abs(cs[fin] - co["scores"][fin]).max() <= 2e-5
+        # the exhaustive search and the list agree on every listed pair
+        ll, qq, cc = np.nonzero(fin)
+        assert np.abs(o["scores"][ll, qq, cand[ll, qq, cc]] - co["scores"][ll, qq, cc]).max(initial=0.0) <= 1e-12
+    # the paper's layer-mean distance (block mode norms)
+    if w.mode == 0:
+        lv = live.min(dim=0).values.contiguous()
+        thr = 0.5 * np.sqrt(w.Dh / (w.T * w.H))
+        lm = rc.rc_match_blocks_layer_mean(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, lv, thr)
+        torch.cuda.synchronize()
+        lg = {k: v.cpu().numpy() for k, v in lm.items()}
+        lo = oracle.layer_mean(d, *bits, lv.cpu().numpy(), thr, want_dist=True)
+        # exact copies (planted with sigma > 0 here, so none) would need the full tolerance
+        parity.check_layer_mean(lg, lo, thr, parity.dist_lookup(lo["dist"], lg["best_idx"]), 0.05 * parity.dist_tol(w.T, w.H, w.Dh))
+    say(f"{w.name}: {rep['n']} queries, {rep['ambiguous']} ambiguous, max score error {rep['max_score_err']:.1e}")
