@@ -401,6 +401,60 @@ done:
 }
 
 /*
+ * Stage 2 exactly as the paper runs it: the layer-mean block distance (block-distance equation of
+ * Sec. IV-A) of the listed candidate pairs only (the blocks of the steps Stage 1 flagged).
+ * cand[q][c] is a pool index or -1, the same list for every layer; live is [P].  Each listed pair
+ * is computed from scratch by subtracting and squaring; entries that are -1, out of range or dead
+ * get +inf.  best = smallest distance, ties to the lowest pool index; match iff best <= thr.
+ */
+int rc_oracle_candidate_distances(int dtype, int L, int T, int H, int Dh,
+                                  const uint16_t* kq, const uint16_t* vq, int64_t q_layer_stride, int64_t Q,
+                                  const uint16_t* kp, const uint16_t* vp, int64_t p_layer_stride, int64_t P,
+                                  const int32_t* cand, int64_t C, const uint8_t* live, double thr,
+                                  double* dist, int32_t* best_idx, double* best_dist, int32_t* match_idx) {
+  if (L <= 0) return 1;
+  if (bad_shape(L, T, H, Dh, q_layer_stride, Q) || bad_shape(L, T, H, Dh, p_layer_stride, P) || C < 0) return 1;
+  if (!best_idx || !best_dist || !match_idx || (C > 0 && (!cand || !dist))) return 1;
+  const int64_t D = (int64_t)T * H * Dh;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t q = 0; q < Q; ++q) {
+    double* buf = (double*)malloc(sizeof(double) * 4 * (size_t)D);
+    if (!buf) { err = 2; continue; }
+    int32_t bi = -1;
+    double bd = INFINITY;
+    for (int64_t c = 0; c < C; ++c) {
+      const int32_t pidx = cand[q * C + c];
+      double d = INFINITY;
+      if (pidx >= 0 && pidx < P && (!live || live[pidx])) {
+        double sum = 0.0;
+        for (int l = 0; l < L; ++l) {
+          decode_block(dtype, kq + (int64_t)l * q_layer_stride + q * D, D, buf);
+          decode_block(dtype, vq + (int64_t)l * q_layer_stride + q * D, D, buf + D);
+          decode_block(dtype, kp + (int64_t)l * p_layer_stride + (int64_t)pidx * D, D, buf + 2 * D);
+          decode_block(dtype, vp + (int64_t)l * p_layer_stride + (int64_t)pidx * D, D, buf + 3 * D);
+          double sk = 0.0, sv = 0.0;
+          for (int64_t i = 0; i < D; ++i) {
+            const double a = buf[i] - buf[2 * D + i], b = buf[D + i] - buf[3 * D + i];
+            sk += a * a;
+            sv += b * b;
+          }
+          sum += (sqrt(sk) + sqrt(sv)) / (2.0 * T * H);
+        }
+        d = sum / L;
+        if (d < bd || (d == bd && pidx < bi)) { bd = d; bi = pidx; }
+      }
+      dist[q * C + c] = d;
+    }
+    best_idx[q] = bi;
+    best_dist[q] = bd;
+    match_idx[q] = (bi >= 0 && bd <= thr) ? bi : -1;
+    free(buf);
+  }
+  return err;
+}
+
+/*
  * Percentile-based adaptive threshold (Sec. IV-A, "Percentile-based Adaptive Thresholding"; the
  * parameter paragraph of the evaluation: the p % of the candidates with the lowest distances are
  * kept).  From the distances collected during warm-up the threshold is the p-th percentile by

@@ -202,6 +202,32 @@ def layer_mean(dtype, kq, vq, kp, vp, live, thr, want_dist=False):
     return out
 
 
+def candidate_distances(dtype, kq, vq, kp, vp, cand, live, thr):
+    """Layer-mean distance of the listed pairs; cand is [Q][C] (pool index or -1), live [P] or None.
+
+    Returns dict(dist [Q][C], best_idx, best_dist, match_idx)."""
+    kq, vq, kp, vp = _kv(kq), _kv(vq), _kv(kp), _kv(vp)
+    L, Q, T, H, Dh = kq.shape
+    P = kp.shape[1]
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    assert cand.ndim == 2 and cand.shape[0] == Q
+    C = cand.shape[1]
+    if live is not None:
+        live = np.ascontiguousarray(live, dtype=np.uint8)
+        assert live.shape == (P,)
+    D = T * H * Dh
+    dist = np.zeros((Q, C), dtype=np.float64)
+    best_idx = np.zeros(Q, dtype=np.int32)
+    match_idx = np.zeros(Q, dtype=np.int32)
+    best = np.zeros(Q, dtype=np.float64)
+    rc = _load().rc_oracle_candidate_distances(
+        ctypes.c_int(dtype), ctypes.c_int(L), ctypes.c_int(T), ctypes.c_int(H), ctypes.c_int(Dh),
+        _p(kq), _p(vq), ctypes.c_int64(Q * D), ctypes.c_int64(Q), _p(kp), _p(vp), ctypes.c_int64(P * D), ctypes.c_int64(P),
+        _p(cand), ctypes.c_int64(C), _p(live), ctypes.c_double(thr), _p(dist), _p(best_idx), _p(best), _p(match_idx))
+    _check(rc, "candidate_distances")
+    return dict(dist=dist, best_idx=best_idx, best_dist=best, match_idx=match_idx)
+
+
 def pat_threshold(samples, p):
     """Nearest-rank p-th percentile of the finite float32 samples.  Returns (threshold float32, n_finite)."""
     samples = np.ascontiguousarray(samples, dtype=np.float32).ravel()

@@ -617,3 +617,43 @@ def test_pool_admit_closes_the_loop(oracle):
     assert again["match_idx"].tolist() == [5, 9, -1, -1]
     s = oracle.match(0, oracle.BLOCK, a["kq"], a["vq"], a["kp"], a["vp"], np.tile(live, (w.L, 1)), 0.95)
     assert (s["best_score"][:, :2] == 1.0).all() and (s["match_idx"][:, :2] == np.array([5, 9])).all()
+
+
+# ---- Stage 2 as the paper runs it: layer-mean distance of listed candidate pairs
+
+def test_candidate_distances_vs_matrix_and_rules(oracle):
+    rng = np.random.RandomState(31)
+    L, Q, P, T, H, Dh = 3, 5, 9, 2, 2, 8
+    kq, vq, kp, vp = (rand_kv(rng, L, n, T, H, Dh, 0) for n in (Q, Q, P, P))
+    live = np.ones(P, dtype=np.uint8)
+    live[4] = 0
+    full = oracle.layer_mean(0, kq, vq, kp, vp, None, 0.0, want_dist=True)["dist"]      # pinned separately
+    cand = rng.randint(0, P, size=(Q, 6)).astype(np.int32)
+    cand[:, 1] = -1                       # empty slot
+    cand[0, 0] = P + 3                    # out of range
+    cand[1, 2] = 4                        # dead
+    cand[2, 3] = cand[2, 4]               # listed twice
+    cand[3, :] = -1                       # empty list
+    r = oracle.candidate_distances(0, kq, vq, kp, vp, cand, live, 1e9)
+    for q in range(Q):
+        for c in range(6):
+            p = cand[q, c]
+            if p < 0 or p >= P or not live[p]:
+                assert np.isposinf(r["dist"][q, c])
+            else:
+                assert r["dist"][q, c] == pytest.approx(full[q, p], rel=1e-14)
+    assert r["best_idx"][3] == -1 and np.isposinf(r["best_dist"][3]) and r["match_idx"][3] == -1
+    for q in (0, 1, 2, 4):
+        valid = [(full[q, p], p) for p in cand[q] if 0 <= p < P and live[p]]
+        assert (r["best_dist"][q], r["best_idx"][q]) == pytest.approx(min(valid))
+    # the hand-worked two-layer case through a list
+    c = json.load(open(os.path.join(GOLD, "layer_mean_handworked.json")))["cases"][1]
+    a = [layers(c[n], c["T"], c["H"], c["Dh"], 0) for n in ("kq", "vq", "kp", "vp")]
+    r = oracle.candidate_distances(0, *a, np.array([[0, -1, 0]], dtype=np.int32), None, 4.5)
+    assert r["dist"][0].tolist() == [4.5, np.inf, 4.5] and r["match_idx"][0] == 0          # inclusive threshold
+    assert oracle.candidate_distances(0, *a, np.array([[0]], dtype=np.int32), None, 4.49)["match_idx"][0] == -1
+    # ties go to the lowest pool index whatever the order in the list
+    kp2 = np.concatenate([kp[:, :1]] * 3, axis=1)
+    vp2 = np.concatenate([vp[:, :1]] * 3, axis=1)
+    r = oracle.candidate_distances(0, kq, vq, kp2, vp2, np.tile(np.array([[2, 1, 0]], dtype=np.int32), (Q, 1)), None, 1e9)
+    assert (r["best_idx"] == 0).all()
