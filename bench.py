@@ -184,6 +184,27 @@ def main():
             "ms": cand_ms, "gb_per_s": cand_bytes / (cand_ms * 1e-3) / 1e9,
             "hbm_frac": cand_bytes / (cand_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "pairs_per_s": L * Q * C / (cand_ms * 1e-3)}
+    if args.candidates > 0 and P > 0:
+        # Stage 2 as the paper runs it: layer-mean distance of C listed pairs per query, one list for all layers
+        C = args.candidates
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(54321)
+        cand1 = torch.randint(0, P, (Q, C), generator=gen, device=dev, dtype=torch.int32)
+        lv1 = pr["live"].min(dim=0).values.contiguous()
+        cdo = rc.rc_candidate_distances(pr["kq"], pr["vq"], pr["kp"], pr["vp"], lv1, cand1, 0.5)
+        ws_cd = torch.empty(max(16, rc.lib().rc_candidate_distances_workspace_size(rc.ctypes.byref(rc.kv_desc(pr["kq"])), Q, C)),
+                            dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            rc.rc_candidate_distances(pr["kq"], pr["vq"], pr["kp"], pr["vp"], lv1, cand1, 0.5, workspace=ws_cd, out=cdo)
+        e1.record()
+        torch.cuda.synchronize()
+        cd_ms = e0.elapsed_time(e1) / args.steps
+        cd_bytes = L * Q * C * w.block_bytes
+        kernels[f"rc_candidate_distances(C={C}, not in the step)"] = {
+            "ms": cd_ms, "gb_per_s": cd_bytes / (cd_ms * 1e-3) / 1e9,
+            "hbm_frac": cd_bytes / (cd_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "pairs_per_s": Q * C / (cd_ms * 1e-3)}
     if args.layer_mean and P > 0 and w.mode == 0:
         # the paper's own measure (not part of the step): layer-mean Euclidean distance, one decision per block
         lv = pr["live"].min(dim=0).values.contiguous()

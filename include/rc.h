@@ -215,6 +215,35 @@ rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const rc_kv_desc* 
                                      float* second_dist,
                                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Bytes of DEVICE workspace rc_candidate_distances needs (0 on bad arguments). */
+size_t rc_candidate_distances_workspace_size(const rc_kv_desc* qdesc, int64_t Q, int64_t C);
+
+/*
+ * Stage 2 exactly as the paper runs it (Sec. IV-A): the layer-mean block distance
+ * dist(q, p) = (1/L) sum_i (|K_i[q] - K_i[p]| + |V_i[q] - V_i[p]|) / (2 T H)  of the listed
+ * candidate pairs only (the blocks of the steps that Stage 1 flagged), one decision per query
+ * block shared by all layers.  HBM bound: every listed pool block is streamed once per layer
+ * against the query block; since both are in registers anyway the differences are formed
+ * directly (exact in fp32) instead of through the expansion with cached norms, so no norms
+ * are taken and near-duplicate pairs lose no digits.
+ *
+ *   cand            DEVICE int32 [Q][C]: pool index, or -1 for an empty slot; the same list for
+ *                   every layer.  Entries outside [0, P) and dead blocks get +inf.
+ *   pool_live       DEVICE uint8 [P], NULL = all live
+ *   dist            DEVICE float [Q][C]
+ *   best_idx        DEVICE int32 [Q]: nearest listed block, equal distances to the lowest pool
+ *                   index; -1 if the list has no valid entry.  best_dist: +inf if none.
+ *   match_idx       DEVICE int32 [Q]: best_idx if best_dist <= threshold, else -1
+ *   workspace       DEVICE, >= rc_candidate_distances_workspace_size() bytes, 16-byte aligned, scratch
+ * n_layers must be >= 1.  Q == 0 launches nothing; C == 0 or P == 0 writes -1 / +inf.
+ */
+rc_status rc_candidate_distances(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc,
+                                 const void* kq, const void* vq, int64_t Q,
+                                 const void* kp, const void* vp, int64_t P,
+                                 const uint8_t* pool_live, const int32_t* cand, int64_t C, float threshold,
+                                 float* dist, int32_t* best_idx, float* best_dist, int32_t* match_idx,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of DEVICE workspace rc_pat_threshold needs (a constant, about 4 KB). */
 size_t rc_pat_workspace_size(void);
 

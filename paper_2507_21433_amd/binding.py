@@ -19,7 +19,7 @@ RC_SCORE_BLOCK, RC_SCORE_PER_HEAD_ALL = 0, 1
 EXPORTS = ("rc_block_norms", "rc_match_workspace_size", "rc_match_blocks", "rc_remap_workspace_size",
            "rc_remap_block_table", "rc_score_candidates", "rc_layer_mean_workspace_size", "rc_match_blocks_layer_mean",
            "rc_pat_workspace_size", "rc_pat_threshold", "rc_apply_threshold", "rc_pool_admit_workspace_size", "rc_pool_admit",
-           "rc_last_error", "rc_version")
+           "rc_candidate_distances_workspace_size", "rc_candidate_distances", "rc_last_error", "rc_version")
 
 
 class RcError(RuntimeError):
@@ -76,6 +76,10 @@ def lib():
         L.rc_pool_admit_workspace_size.restype = sz
         L.rc_pool_admit.argtypes = [dp, dp, i32, vp, vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.rc_pool_admit.restype = i32
+        L.rc_candidate_distances_workspace_size.argtypes = [dp, i64, i64]
+        L.rc_candidate_distances_workspace_size.restype = sz
+        L.rc_candidate_distances.argtypes = [dp, dp, vp, vp, i64, vp, vp, i64, vp, vp, i64, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.rc_candidate_distances.restype = i32
         L.rc_last_error.restype = ctypes.c_char_p
         L.rc_version.restype = i32
         _lib = L
@@ -299,4 +303,29 @@ def rc_pool_admit(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, pool_live, match_i
                                _ptr(kp), _ptr(vp), P, _ptr(p_ksq), _ptr(p_vsq), _ptr(pool_live), _ptr(match_idx),
                                _ptr(out["slot_of_query"]), _ptr(out["n_admitted"]), _ptr(workspace), workspace.numel(),
                                _stream()))
+    return out
+
+
+def rc_candidate_distances(kq, vq, kp, vp, pool_live, cand, threshold, workspace=None, out=None):
+    """Layer-mean distance of the listed pairs, cand [Q][C].  Returns dict(dist [Q][C], best_idx, best_dist, match_idx)."""
+    _dev(kq, vq, kp, vp, pool_live, cand)
+    qd, pd = kv_desc(kq), kv_desc(kp)
+    assert kv_desc(vq).layer_stride == qd.layer_stride and kv_desc(vp).layer_stride == pd.layer_stride
+    Q, P = kq.shape[1], kp.shape[1]
+    assert cand.dtype == torch.int32 and cand.dim() == 2 and cand.shape[0] == Q and cand.is_contiguous()
+    C = cand.shape[1]
+    if pool_live is not None:
+        assert pool_live.dtype == torch.uint8 and pool_live.shape == (P,) and pool_live.is_contiguous()
+    if workspace is None:
+        workspace = torch.empty(max(16, lib().rc_candidate_distances_workspace_size(ctypes.byref(qd), Q, C)),
+                                dtype=torch.uint8, device=kq.device)
+    if out is None:
+        out = dict(dist=torch.empty((Q, C), dtype=torch.float32, device=kq.device),
+                   best_idx=torch.empty((Q,), dtype=torch.int32, device=kq.device),
+                   best_dist=torch.empty((Q,), dtype=torch.float32, device=kq.device),
+                   match_idx=torch.empty((Q,), dtype=torch.int32, device=kq.device))
+    _check(lib().rc_candidate_distances(ctypes.byref(qd), ctypes.byref(pd), _ptr(kq), _ptr(vq), Q, _ptr(kp), _ptr(vp), P,
+                                        _ptr(pool_live), _ptr(cand), C, float(threshold), _ptr(out["dist"]),
+                                        _ptr(out["best_idx"]), _ptr(out["best_dist"]), _ptr(out["match_idx"]),
+                                        _ptr(workspace), workspace.numel(), _stream()))
     return out
