@@ -1,20 +1,24 @@
 """Comparison rule between the HIP path and the CPU oracle (test helper, no GPU code).
 
-Scores agree to 2e-3 absolute.  A query is *ambiguous* when the oracle's best score is
-within 2e-3 of the threshold or of the runner-up; only there may indices differ, and
-then the GPU's choice must still be within 2e-3 of the oracle's best.  Everything else
-is bit-exact.
+Scores agree to 2e-3 absolute (the bar; the observed error is below 1e-5).  A query is
+*ambiguous* when the oracle's best score is within AMB of the threshold or of the runner-up;
+only there may indices differ, and then the GPU's choice must still be within AMB of the
+oracle's best.  AMB is 1e-4, ten times the observed error and twenty times tighter than the
+bar, so that the index comparison stays sharp on workloads whose unmatched queries have
+many nearly equal partners.  Everything else is bit-exact.
 """
 import numpy as np
 
 TOL = 2e-3
+AMB = 1e-4
 
 
-def check_match(gpu, orc, tau, score_at_gpu_idx, tol=TOL):
+def check_match(gpu, orc, tau, score_at_gpu_idx, tol=TOL, amb=None):
     """gpu / orc: dicts of numpy arrays [L][Q]; score_at_gpu_idx: oracle score of (q, gpu best_idx), NaN where idx < 0.
 
     Returns a report dict; raises AssertionError with a description on a violation.
     """
+    amb = min(tol, AMB) if amb is None else amb
     gi, gs, gm = gpu["best_idx"], gpu["best_score"].astype(np.float64), gpu["match_idx"]
     oi, os_, om, o2 = orc["best_idx"], orc["best_score"], orc["match_idx"], orc["second_score"]
     has = oi >= 0
@@ -25,18 +29,18 @@ def check_match(gpu, orc, tau, score_at_gpu_idx, tol=TOL):
     err = np.abs(gs[has] - score_at_gpu_idx[has])
     assert err.size == 0 or err.max() <= tol, f"best_score off by {err.max():.3e}"
 
-    near_tau = np.abs(os_ - tau) <= tol
-    near_tie = (os_ - o2) <= tol
-    amb = has & (near_tau | near_tie)
-    clear = has & ~amb
+    near_tau = np.abs(os_ - tau) <= amb
+    near_tie = (os_ - o2) <= amb
+    amb_set = has & (near_tau | near_tie)
+    clear = has & ~amb_set
     # 2. clear queries: bit-exact decisions
     bad = clear & ((gi != oi) | (gm != om))
     assert not bad.any(), f"{int(bad.sum())} non-ambiguous queries differ, first at {np.argwhere(bad)[0]}"
     # 3. ambiguous queries: the GPU's pick is as good as the oracle's within tol, decision consistent
-    if amb.any():
-        assert (os_[amb] - score_at_gpu_idx[amb] <= tol).all(), "ambiguous pick is worse than the best by more than tol"
-        assert ((gm[amb] == -1) | (gm[amb] == gi[amb])).all()
-        decided = amb & ~near_tau
+    if amb_set.any():
+        assert (os_[amb_set] - score_at_gpu_idx[amb_set] <= amb).all(), "ambiguous pick is worse than the best by more than the band"
+        assert ((gm[amb_set] == -1) | (gm[amb_set] == gi[amb_set])).all()
+        decided = amb_set & ~near_tau
         assert np.array_equal(gm[decided] >= 0, om[decided] >= 0), "threshold decision differs away from tau"
     # 4. GPU-internal consistency of the decision with its own score
     assert np.array_equal(gm >= 0, has & (gpu["best_score"] >= np.float32(tau)))
@@ -45,10 +49,10 @@ def check_match(gpu, orc, tau, score_at_gpu_idx, tol=TOL):
         fin = np.isfinite(o2)
         assert np.array_equal(np.isfinite(g2), fin)
         assert fin.sum() == 0 or np.abs(g2[fin] - o2[fin]).max() <= tol, "runner-up score off"
-    return dict(n=int(has.sum()), ambiguous=int(amb.sum()), near_tau=int((has & near_tau).sum()),
+    return dict(n=int(has.sum()), ambiguous=int(amb_set.sum()), near_tau=int((has & near_tau).sum()),
                 near_tie=int((has & near_tie).sum()), max_score_err=float(err.max()) if err.size else 0.0,
                 matched=int((gm >= 0).sum()),
-                ambiguous_list=[tuple(int(x) for x in a) for a in np.argwhere(amb)[:16]])
+                ambiguous_list=[tuple(int(x) for x in a) for a in np.argwhere(amb_set)[:16]])
 
 
 def score_lookup(scores, idx):
