@@ -183,9 +183,8 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // one pool tile stay together: the second one finds the pool slice in the L2 only if it follows
   // closely); later rounds inherit the spread.  Nothing else changes.  Measured on one box against
   // an unspread start: 3-5 % faster with one query tile (Q = 256), 3.5 % and 5-10 % with four
-  // (Q = 1024, pools of 16 K and 48 K blocks); per-head mode with its 128-row tiles gains nothing
-  // and is left alone.
-  if (MODE != 1 && wg < p.stagger_wgs)
+  // (Q = 1024, pools of 16 K and 48 K blocks), no difference in per-head mode.
+  if (wg < p.stagger_wgs)
     for (int i = 0; i < (((slot % p.chunk) / p.nqt) & 15) * p.stagger_unit; ++i) __builtin_amdgcn_s_sleep(16);
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -404,16 +403,21 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
       }
   };
 
-  // per-head mode: running minimum over heads of the finished head score; acc restarts at 0
-  f32x16 smin[MODE != 1 ? 1 : TP][MODE != 1 ? 1 : TQ];
+  // per-head mode: running minimum over heads of the finished head score; acc restarts at 0.
+  // A second fp32 register tile does not fit next to a 256x256 accumulator tile, so the running
+  // minimum is kept as 16-bit fixed point (score * 32767 rounded to nearest, two per register,
+  // packed min): resolution 3.1e-5, error at most 1.6e-5 on a score in [-1, 1].
+  constexpr int SM = (MODE == 1) ? 1 : 0;
+  int smin[SM ? TP : 1][SM ? TQ : 1][8];
   if (MODE == 1) {
 #pragma unroll
     for (int i = 0; i < TP; ++i)
 #pragma unroll
       for (int j = 0; j < TQ; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) smin[i][j][r] = INFINITY;
+        for (int r = 0; r < 8; ++r) smin[SM ? i : 0][SM ? j : 0][r] = 0x7fff7fff;
   }
+  typedef short i16x2 __attribute__((ext_vector_type(2)));
   auto finish_head = [&](int head) {
     float rq[TQ], fq[TQ];
     query_scales(head, rq, fq);
@@ -426,11 +430,17 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 #pragma unroll
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float sc = acc[i][j][4 * g + e] * (fq[j] * fp[e]);
-            smin[MODE != 1 ? 0 : i][MODE != 1 ? 0 : j][4 * g + e] =
-                fminf(smin[MODE != 1 ? 0 : i][MODE != 1 ? 0 : j][4 * g + e], sc);
+          for (int e = 0; e < 4; e += 2) {
+            const float s0 = acc[i][j][4 * g + e] * (fq[j] * fp[e]), s1 = acc[i][j][4 * g + e + 1] * (fq[j] * fp[e + 1]);
+            // |score| <= 1 up to rounding; the clamp keeps the conversion inside 16 bits
+            const int q0 = (int)rintf(fminf(fmaxf(s0, -1.f), 1.f) * 32767.f), q1 = (int)rintf(fminf(fmaxf(s1, -1.f), 1.f) * 32767.f);
+            const i16x2 nw = {(short)q0, (short)q1};
+            int& slot = smin[SM ? i : 0][SM ? j : 0][2 * g + (e >> 1)];
+            const i16x2 old = __builtin_bit_cast(i16x2, slot);
+            const i16x2 mn = {old[0] < nw[0] ? old[0] : nw[0], old[1] < nw[1] ? old[1] : nw[1]};
+            slot = __builtin_bit_cast(int, mn);
             acc[i][j][4 * g + e] = 0.f;
+            acc[i][j][4 * g + e + 1] = 0.f;
           }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -592,7 +602,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
             if (MODE == 0)
               sc = acc[i][j][4 * g + e] * (fq[j] * fp[e]) + bias[e];
             else
-              sc = smin[MODE != 1 ? 0 : i][MODE != 1 ? 0 : j][4 * g + e] + bias[e];
+              sc = (float)__builtin_bit_cast(i16x2, smin[SM ? i : 0][SM ? j : 0][2 * g + (e >> 1)])[e & 1] / 32767.f + bias[e];
             top2_push(sc, p0 + row + e, best[j], bidx[j], second[j]);
           }
         __builtin_amdgcn_sched_barrier(0);
@@ -791,14 +801,15 @@ inline int compute_units() {
 }
 constexpr int kStaggerUnit = 6;  // x 1024 clocks per tile index, one to two pipeline steps (flat optimum between 3 and 8)
 
-// Tile shapes.  Block mode keeps a 128x128 accumulator tile per wave (all 256 accumulation
-// registers of a lane); per-head-all mode needs a second register tile for the running minimum
-// over heads and therefore uses half the rows.
+// Tile shape: a 128x128 accumulator tile per wave (all 256 accumulation registers of a lane) in
+// every mode.  What is carried across phases is kept out of the fp32 register budget: the
+// per-head mode packs its running minimum into 16-bit fixed point, the layer-mean mode keeps
+// its running sum in the workspace.
 struct TileShape {
   int bp, bq;
 };
 constexpr TileShape kBlockTile = {256, 256};
-constexpr TileShape kHeadTile = {128, 256};
+constexpr TileShape kHeadTile = {256, 256};
 
 inline TileShape tile_for(int mode) { return mode == RC_SCORE_BLOCK ? kBlockTile : kHeadTile; }
 
