@@ -29,8 +29,9 @@ def check_match(gpu, orc, tau, score_at_gpu_idx, tol=TOL, amb=None):
     err = np.abs(gs[has] - score_at_gpu_idx[has])
     assert err.size == 0 or err.max() <= tol, f"best_score off by {err.max():.3e}"
 
-    near_tau = np.abs(os_ - tau) <= amb
-    near_tie = (os_ - o2) <= amb
+    with np.errstate(invalid="ignore"):          # -inf - -inf where a layer has no live block
+        near_tau = np.abs(os_ - tau) <= amb
+        near_tie = (os_ - o2) <= amb
     amb_set = has & (near_tau | near_tie)
     clear = has & ~amb_set
     # 2. clear queries: bit-exact decisions

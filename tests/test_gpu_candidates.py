@@ -45,7 +45,8 @@ def compare(gpu, orc, cand, tau, tol=parity.TOL, amb=AMB):
     best = orc["best_score"]
     # runner-up among candidates that name a different pool block than the best
     other = np.where((cand != orc["best_idx"][..., None]) & fin, os_, -np.inf).max(axis=-1) if cand.shape[-1] else np.full(best.shape, -np.inf)
-    amb = (best - other <= amb) | (np.abs(best - tau) <= amb)
+    with np.errstate(invalid="ignore"):          # -inf - -inf for a list without a valid entry
+        amb = (best - other <= amb) | (np.abs(best - tau) <= amb)
     clear = ~amb
     assert np.array_equal(gpu["best_idx"][clear], orc["best_idx"][clear])
     assert np.array_equal(gpu["match_idx"][clear], orc["match_idx"][clear])
@@ -136,7 +137,8 @@ def compare_distances(gpu, orc, cand, thr, tol):
     assert err <= tol, f"distance off by {err:.3e}"
     best = orc["best_dist"]
     other = np.where((cand != orc["best_idx"][:, None]) & fin, od, np.inf).min(axis=-1) if cand.shape[-1] else np.full(best.shape, np.inf)
-    clear = ~((other - best <= tol) | (np.abs(best - thr) <= tol))
+    with np.errstate(invalid="ignore"):          # inf - inf for a list without a valid entry
+        clear = ~((other - best <= tol) | (np.abs(best - thr) <= tol))
     assert np.array_equal(gpu["best_idx"][clear], orc["best_idx"][clear])
     assert np.array_equal(gpu["match_idx"][clear], orc["match_idx"][clear])
     has = orc["best_idx"] >= 0
