@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--layer-mean", type=int, default=1, help="also time the layer-mean distance entry point (0 = skip)")
     ap.add_argument("--pat-samples", type=int, default=1 << 22, help="warm-up sample size for the percentile threshold (0 = skip)")
     ap.add_argument("--admit", type=int, default=1, help="also time the admission of unmatched blocks into the pool (0 = skip)")
+    ap.add_argument("--streaming", type=int, default=4, help="consecutive decoding steps of the steady-state loop (0 = skip)")
     ap.add_argument("--candidates", type=int, default=16,
                     help="C of the candidate-restricted scoring timed beside the step (0 = skip)")
     args = ap.parse_args()
@@ -265,6 +266,55 @@ def main():
         kernels["rc_pool_admit(not in the step)"] = {
             "ms": ad_ms, "admitted_blocks": n_adm, "gb_per_s": ad_bytes / (ad_ms * 1e-3) / 1e9,
             "hbm_frac": ad_bytes / (ad_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    streaming = None
+    if args.streaming > 0 and w.mode == 0 and P >= (args.streaming + 1) * Q:
+        # the paper's steady state (not the timed step above): consecutive decoding steps over one pool with the
+        # paper's own measure.  Per step: norms of the new blocks, layer-mean search, decision against a threshold
+        # that lives on the device, remap of a layer-shared table, admission of the blocks that found no partner.
+        S = args.streaming
+        lv = pr["live"].min(dim=0).values.contiguous().clone()
+        lv[P - S * Q:] = 0                                            # room for S steps of admissions
+        thr_dev = torch.full((1,), 0.5, dtype=torch.float32, device=dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4242)
+        n_copy = int(0.3 * Q)
+        steps_kq, steps_vq = [], []
+        for sidx in range(S):                                         # inputs of every step, built before the clock starts
+            kq_s = torch.randn(pr["kq"].shape, generator=gen, device=dev, dtype=torch.float32).to(pr["kq"].dtype)
+            vq_s = torch.randn(pr["vq"].shape, generator=gen, device=dev, dtype=torch.float32).to(pr["vq"].dtype)
+            tgt = torch.randint(0, P - S * Q, (n_copy,), generator=gen, device=dev)
+            kq_s[:, :n_copy] = (pr["kp"][:, tgt].float() + w.sigma * torch.randn((L, n_copy) + tuple(pr["kp"].shape[2:]), generator=gen, device=dev)).to(pr["kq"].dtype)
+            vq_s[:, :n_copy] = (pr["vp"][:, tgt].float() + w.sigma * torch.randn((L, n_copy) + tuple(pr["vp"].shape[2:]), generator=gen, device=dev)).to(pr["vq"].dtype)
+            steps_kq.append(kq_s)
+            steps_vq.append(vq_s)
+        ws_lm2 = torch.empty(max(16, rc.rc_layer_mean_workspace_size(pr["kq"], Q, P)), dtype=torch.uint8, device=dev)
+        ws_ad2 = torch.empty(max(16, rc.lib().rc_pool_admit_workspace_size(Q, P)), dtype=torch.uint8, device=dev)
+        ws_rm2 = torch.empty(rc.rc_remap_workspace_size(1, 1, Q, Q, P + Q), dtype=torch.uint8, device=dev)
+        table = (P + torch.arange(Q, dtype=torch.int32, device=dev)).reshape(1, 1, Q).contiguous()
+        qids = (P + torch.arange(Q, dtype=torch.int32, device=dev)).contiguous()
+        refc = torch.ones((1, P + Q), dtype=torch.int32, device=dev)
+        lm2, ad2, rm2 = None, None, None
+        dec = torch.empty((Q,), dtype=torch.int32, device=dev)
+        shared, admitted = [], []
+        torch.cuda.synchronize()
+        e0.record()
+        for sidx in range(S):
+            rc.rc_block_norms(steps_kq[sidx], steps_vq[sidx], 0, qk, qv)
+            lm2 = rc.rc_match_blocks_layer_mean(steps_kq[sidx], steps_vq[sidx], qk, qv, pr["kp"], pr["vp"], pk, pv, lv,
+                                                float("inf"), workspace=ws_lm2, out=lm2)
+            rc.rc_apply_threshold(lm2["best_idx"], lm2["best_dist"], thr_dev, dec)
+            rm2 = rc.rc_remap_block_table(table, qids, None, dec.reshape(1, Q), P, P + Q, refc, workspace=ws_rm2, out=rm2)
+            ad2 = rc.rc_pool_admit(steps_kq[sidx], steps_vq[sidx], qk, qv, pr["kp"], pr["vp"], pk, pv, lv, dec,
+                                   workspace=ws_ad2, out=ad2)
+            shared.append((dec >= 0).sum())
+            admitted.append(ad2["n_admitted"].clone())
+        e1.record()
+        torch.cuda.synchronize()
+        st_ms = e0.elapsed_time(e1) / S
+        streaming = {"steps": S, "ms_per_step": st_ms, "pairs_per_s": pairs / (st_ms * 1e-3),
+                     "shared_per_step": [int(x.item()) for x in shared],
+                     "admitted_per_step": [int(x.item()) for x in admitted],
+                     "what": "norms(Q) + layer-mean search + device-threshold decision + layer-shared remap + admission"}
     matched = int((out["match_idx"] >= 0).sum().item())
     n_remapped = int(res["n_remapped"].sum().item())
 
@@ -285,6 +335,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
+        "streaming": streaming,
         "matched_queries": matched, "remapped_entries": n_remapped,
     }
     print(json.dumps(line), flush=True)
