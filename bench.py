@@ -267,7 +267,9 @@ def main():
             "ms": ad_ms, "admitted_blocks": n_adm, "gb_per_s": ad_bytes / (ad_ms * 1e-3) / 1e9,
             "hbm_frac": ad_bytes / (ad_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
     streaming = None
-    if args.streaming > 0 and w.mode == 0 and P >= (args.streaming + 1) * Q:
+    torch.cuda.empty_cache()
+    stream_bytes = 3 * args.streaming * L * Q * w.block_bytes       # the steps' inputs plus fp32 temporaries while drawing them
+    if args.streaming > 0 and w.mode == 0 and P >= (args.streaming + 1) * Q and torch.cuda.mem_get_info()[0] > stream_bytes + (8 << 30):
         # the paper's steady state (not the timed step above): consecutive decoding steps over one pool with the
         # paper's own measure.  Per step: norms of the new blocks, layer-mean search, decision against a threshold
         # that lives on the device, remap of a layer-shared table, admission of the blocks that found no partner.
