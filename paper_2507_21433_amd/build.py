@@ -13,6 +13,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unused-const-variable",
+    "-Wno-inline-asm",   # the m0 clobber of the direct-to-LDS loads is deliberate (m0 is set inside the same asm block)
 ]
 
 

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kGatherThreads) void remap_gather_kernel(
     int32_t* __restrict__ partial, const int32_t* refcount_in, int32_t* refcount_out, long long rc_chunk,
     int rc_vec) {
   extern __shared__ int hist[];  // Q bins
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   const long long l = blockIdx.y, g = blockIdx.x, G = gridDim.x;
   for (int q = tid; q < Q; q += kGatherThreads) hist[q] = 0;
   __syncthreads();
