@@ -810,8 +810,15 @@ struct TileShape {
 };
 constexpr TileShape kBlockTile = {256, 256};
 constexpr TileShape kHeadTile = {256, 256};
+// Few query blocks (a decoding step of a handful of requests): a 64-column tile does a quarter of
+// the matrix work per pool slice and leaves the kernel to the speed of the pool stream.
+constexpr TileShape kNarrowTile = {256, 64};
+constexpr TileShape kMidTile = {256, 128};
 
-inline TileShape tile_for(int mode) { return mode == RC_SCORE_BLOCK ? kBlockTile : kHeadTile; }
+inline TileShape tile_for(int mode, int64_t Q) {
+  if (mode != RC_SCORE_BLOCK) return kHeadTile;
+  return Q <= kNarrowTile.bq ? kNarrowTile : Q <= kMidTile.bq ? kMidTile : kBlockTile;
+}
 
 // byte offset of the selection partials inside the layer-mean workspace (after the sums: one
 // 256x256 tile of floats per (group, pool tile, query tile))
@@ -821,7 +828,11 @@ inline size_t layer_mean_part_offset(int groups, int64_t npt, int64_t nqt) {
 
 template <bool BF16>
 void launch_tiles(int mode, const MatchParams& mp, unsigned grid, hipStream_t st) {
-  if (mode == RC_SCORE_BLOCK)
+  if (mode == RC_SCORE_BLOCK && mp.Q <= kNarrowTile.bq)
+    match_tile_kernel<BF16, kNarrowTile.bp, kNarrowTile.bq, 0><<<grid, kThreads, 0, st>>>(mp);
+  else if (mode == RC_SCORE_BLOCK && mp.Q <= kMidTile.bq)
+    match_tile_kernel<BF16, kMidTile.bp, kMidTile.bq, 0><<<grid, kThreads, 0, st>>>(mp);
+  else if (mode == RC_SCORE_BLOCK)
     match_tile_kernel<BF16, kBlockTile.bp, kBlockTile.bq, 0><<<grid, kThreads, 0, st>>>(mp);
   else
     match_tile_kernel<BF16, kHeadTile.bp, kHeadTile.bq, 1><<<grid, kThreads, 0, st>>>(mp);
@@ -834,7 +845,7 @@ extern "C" size_t rc_match_workspace_size(const rc_kv_desc* qdesc, int32_t mode,
   using namespace rc;
   if (!qdesc || Q < 0 || P < 0 || qdesc->n_layers < 0) return 0;
   if (mode != RC_SCORE_BLOCK && mode != RC_SCORE_PER_HEAD_ALL) return 0;
-  const TileShape ts = tile_for(mode);
+  const TileShape ts = tile_for(mode, Q);
   const int64_t npt = (P + ts.bp - 1) / ts.bp;
   const int64_t n = (int64_t)qdesc->n_layers * (npt > 0 ? npt : 1) * Q;
   return (size_t)(n > 0 ? n : 1) * sizeof(Part);
@@ -863,7 +874,7 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
   if (P > 0 && (!kp || !vp || !p_ksq || !p_vsq)) return fail(RC_ERR_INVALID_ARG, "rc_match_blocks: NULL pool pointer");
   if (!aligned16(kq) || !aligned16(vq) || !aligned16(kp) || !aligned16(vp))
     return fail(RC_ERR_INVALID_ARG, "rc_match_blocks: KV pointer not 16-byte aligned");
-  const TileShape ts = tile_for(mode);
+  const TileShape ts = tile_for(mode, Q);
   const int64_t npt = (P + ts.bp - 1) / ts.bp, nqt = (Q + ts.bq - 1) / ts.bq;
   const int64_t total = (int64_t)L * npt * nqt;
   if (Q > 0x7fffffffLL || P > 0x7fffffffLL || total > 0x3fffffffLL || (int64_t)L * Q > 0x7fffffffLL * 128)

@@ -85,7 +85,8 @@ def test_cfg1_tiny(oracle):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("P,Q", [(700, 300), (256, 256), (257, 1), (1, 5), (513, 257)])
+@pytest.mark.parametrize("P,Q", [(700, 300), (256, 256), (257, 1), (1, 5), (513, 257),
+                                 (300, 64), (300, 65), (259, 128), (300, 129)])   # the last four: the edges of the 64- and 128-column tiles
 def test_match_ragged_tiles(oracle, dtype, P, Q):
     # several pool tiles and query tiles with ragged tails, dead blocks, bit-identical pool blocks
     w = synth.scaled(synth.WORKLOADS[2], name=f"ragged_{dtype}_{P}x{Q}", L=2, P=P, Q=Q, dtype=dtype,
