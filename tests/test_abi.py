@@ -99,6 +99,76 @@ def test_remap_validation(lib):
     assert lib.rc_remap_block_table(*args(R=-1)) == 1
 
 
+def test_candidates_validation(lib):
+    q, p = desc(n=4), desc(n=64)
+    args = lambda **kw: [kw.get("qd", ctypes.byref(q)), ctypes.byref(p), kw.get("mode", 0), kw.get("kq", FAKE), FAKE,
+                         kw.get("Q", 4), FAKE, FAKE, FAKE, FAKE, 64, FAKE, FAKE, None, kw.get("cand", FAKE),
+                         kw.get("C", 3), kw.get("tau", 0.9), kw.get("scores", FAKE), FAKE, FAKE, FAKE, None]
+    assert lib.rc_score_candidates(*args(Q=0)) == 0
+    assert lib.rc_score_candidates(*args(C=-1)) == 1
+    assert lib.rc_score_candidates(*args(cand=None)) == 1
+    assert lib.rc_score_candidates(*args(scores=None)) == 1
+    assert lib.rc_score_candidates(*args(kq=ODD)) == 1
+    assert lib.rc_score_candidates(*args(tau=float("nan"))) == 1
+    assert lib.rc_score_candidates(*args(mode=7)) == 2
+    h3 = desc(n=4, H=3)
+    assert lib.rc_score_candidates(*args(qd=ctypes.byref(h3), mode=1)) in (1, 2)      # descriptors differ / heads do not divide 16
+    # layer-mean distance of listed pairs
+    dargs = lambda **kw: [kw.get("qd", ctypes.byref(q)), ctypes.byref(p), kw.get("kq", FAKE), FAKE, kw.get("Q", 4), FAKE, FAKE,
+                          64, None, kw.get("cand", FAKE), kw.get("C", 3), kw.get("thr", 0.5), FAKE, FAKE, FAKE, FAKE,
+                          kw.get("ws", FAKE), kw.get("wsb", 1 << 20), None]
+    assert lib.rc_candidate_distances_workspace_size(ctypes.byref(q), 4, 3) >= 4 * 3 * 4
+    zero_layers = desc(L=0, n=4)
+    assert lib.rc_candidate_distances_workspace_size(ctypes.byref(zero_layers), 4, 3) == 0
+    assert lib.rc_candidate_distances(*dargs(Q=0)) == 0
+    assert lib.rc_candidate_distances(*dargs(wsb=4)) == 3
+    assert lib.rc_candidate_distances(*dargs(thr=float("nan"))) == 1
+    assert lib.rc_candidate_distances(*dargs(cand=None)) == 1
+    assert lib.rc_candidate_distances(*dargs(kq=None)) == 1
+
+
+def test_layer_mean_pat_and_pool_validation(lib):
+    q, p = desc(n=4), desc(n=64)
+    largs = lambda **kw: [kw.get("qd", ctypes.byref(q)), kw.get("pd", ctypes.byref(p)), kw.get("kq", FAKE), FAKE, kw.get("Q", 4),
+                          FAKE, FAKE, FAKE, FAKE, 64, FAKE, FAKE, None, kw.get("thr", 0.5), FAKE, FAKE, FAKE, None,
+                          kw.get("ws", FAKE), kw.get("wsb", 1 << 30), None]
+    assert lib.rc_layer_mean_workspace_size(ctypes.byref(q), 4, 64) >= 65536 * 4
+    assert lib.rc_match_blocks_layer_mean(*largs(Q=0)) == 0
+    assert lib.rc_match_blocks_layer_mean(*largs(wsb=1024)) == 3
+    assert lib.rc_match_blocks_layer_mean(*largs(thr=float("nan"))) == 1
+    assert lib.rc_match_blocks_layer_mean(*largs(kq=None)) == 1
+    z = desc(L=0, n=4)
+    zp = desc(L=0, n=64)
+    assert lib.rc_match_blocks_layer_mean(*largs(qd=ctypes.byref(z), pd=ctypes.byref(zp))) == 1   # a mean over no layers
+    assert b"layers" in lib.rc_last_error()
+    # percentile
+    assert lib.rc_pat_workspace_size() >= 4 * 256 * 4
+    pargs = lambda **kw: [kw.get("s", FAKE), kw.get("n", 10), kw.get("p", 80.0), kw.get("thr", FAKE), None,
+                          kw.get("ws", FAKE), kw.get("wsb", 1 << 16), None]
+    assert lib.rc_pat_threshold(*pargs(p=100.5)) == 1
+    assert lib.rc_pat_threshold(*pargs(p=-1.0)) == 1
+    assert lib.rc_pat_threshold(*pargs(p=float("nan"))) == 1
+    assert lib.rc_pat_threshold(*pargs(n=-1)) == 1
+    assert lib.rc_pat_threshold(*pargs(n=1 << 31)) == 1
+    assert lib.rc_pat_threshold(*pargs(thr=None)) == 1
+    assert lib.rc_pat_threshold(*pargs(s=None)) == 1
+    assert lib.rc_pat_threshold(*pargs(wsb=16)) == 3
+    assert lib.rc_apply_threshold(FAKE, FAKE, 0, FAKE, FAKE, None) == 0
+    assert lib.rc_apply_threshold(FAKE, FAKE, -1, FAKE, FAKE, None) == 1
+    assert lib.rc_apply_threshold(FAKE, FAKE, 5, None, FAKE, None) == 1
+    # admission
+    aargs = lambda **kw: [ctypes.byref(q), ctypes.byref(p), kw.get("mode", 0), kw.get("kq", FAKE), FAKE, 4, FAKE, FAKE, FAKE, FAKE,
+                          64, FAKE, FAKE, kw.get("live", FAKE), kw.get("m", FAKE), FAKE, kw.get("n", FAKE),
+                          kw.get("ws", FAKE), kw.get("wsb", 1 << 20), None]
+    assert lib.rc_pool_admit_workspace_size(4, 64) > 0 and lib.rc_pool_admit_workspace_size(-1, 64) == 0
+    assert lib.rc_pool_admit(*aargs(n=None)) == 1
+    assert lib.rc_pool_admit(*aargs(m=None)) == 1
+    assert lib.rc_pool_admit(*aargs(live=None)) == 1
+    assert lib.rc_pool_admit(*aargs(kq=ODD)) == 1
+    assert lib.rc_pool_admit(*aargs(mode=3)) == 2
+    assert lib.rc_pool_admit(*aargs(wsb=8)) == 3
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(rc, "_lib", None)
     monkeypatch.setattr(rc, "LIB_PATH", str(tmp_path / "missing.so"))
