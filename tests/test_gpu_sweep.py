@@ -89,3 +89,39 @@ def test_random_shape(oracle, case):
         # exact copies (planted with sigma > 0 here, so none) would need the full tolerance
         parity.check_layer_mean(lg, lo, thr, parity.dist_lookup(lo["dist"], lg["best_idx"]), 0.05 * parity.dist_tol(w.T, w.H, w.Dh))
     say(f"{w.name}: {rep['n']} queries, {rep['ambiguous']} ambiguous, max score error {rep['max_score_err']:.1e}")
+
+
+def test_every_entry_point_is_deterministic():
+    # the same inputs give the same bits on every run: no result depends on the order in which workgroups finish
+    w = synth.scaled(synth.WORKLOADS[2], name="determinism", L=3, P=700, Q=130, planted_frac=0.3, R=2, E=500, seed=77)
+    say(w.name)
+    pr = synth.make_problem(w, DEV)
+    lv = pr["live"].min(dim=0).values.contiguous()
+    rng = np.random.RandomState(1)
+    cand3 = torch.as_tensor(rng.randint(-1, w.P, size=(w.L, w.Q, 9)).astype(np.int32), device=DEV)
+    cand2 = torch.as_tensor(rng.randint(-1, w.P, size=(w.Q, 9)).astype(np.int32), device=DEV)
+
+    def run():
+        qk, qv = rc.rc_block_norms(pr["kq"], pr["vq"], 0)
+        pk, pv = rc.rc_block_norms(pr["kp"], pr["vp"], 0)
+        m = rc.rc_match_blocks(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, pr["live"], w.tau, 0)
+        r = rc.rc_remap_block_table(pr["tables"], pr["query_ids"], None, m["match_idx"], w.P, w.NB, pr["refcount"])
+        c = rc.rc_score_candidates(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, pr["live"], cand3, w.tau, 0)
+        d = rc.rc_candidate_distances(pr["kq"], pr["vq"], pr["kp"], pr["vp"], lv, cand2, 0.5)
+        lm = rc.rc_match_blocks_layer_mean(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, lv, 0.5)
+        t = rc.rc_pat_threshold(lm["best_dist"], 60.0)
+        a = rc.rc_apply_threshold(lm["best_idx"], lm["best_dist"], t["threshold"])
+        kp2, vp2, pk2, pv2, lv2 = pr["kp"].clone(), pr["vp"].clone(), pk.clone(), pv.clone(), lv.clone()
+        lv2[::5] = 0
+        ad = rc.rc_pool_admit(pr["kq"], pr["vq"], qk, qv, kp2, vp2, pk2, pv2, lv2, a)
+        torch.cuda.synchronize()
+        outs = [qk, qv, pk, pv, a, kp2, vp2, pk2, pv2, lv2]
+        for dct in (m, r, c, d, lm, t, ad):
+            outs += [dct[k] for k in sorted(dct)]
+        return [o.clone() for o in outs]
+
+    first = run()
+    for _ in range(3):
+        again = run()
+        for x, y in zip(first, again):
+            assert torch.equal(x.view(torch.uint8) if x.is_floating_point() else x, y.view(torch.uint8) if y.is_floating_point() else y)
