@@ -10,11 +10,16 @@
 // One workgroup (4 waves, one per SIMD) owns a BP x BQ tile of S for the whole reduction (no
 // split-K, so the selection can be fused); each wave holds a (BP/2) x (BQ/2) accumulator tile.
 // Operand slices of 64 elements (128 bytes per block, one L2 line) go global -> LDS with
-// direct-to-LDS 16-byte buffer loads.  The workload is HBM-bound when few queries share a pool
-// block, and what bounds it then is the number of pool bytes in flight per compute unit, so all
-// of the 160 KB of LDS is ring buffer: three stages for the pool slices (two always in flight)
-// and two for the query slices, which come from the L2.  The 16-byte chunks of an LDS row are
-// XOR-swizzled by the row number so that fragment reads spread over all banks.
+// direct-to-LDS 16-byte buffer loads.  With a 256 x 256 tile all of the 160 KB of LDS is ring
+// buffer: three stages for the pool slices (two always in flight) and two for the query slices,
+// which come from the L2.  What bounds the kernel is the rate at which the L2 delivers those
+// slices to the compute units (a pool line that misses costs more than a query line that hits),
+// not HBM and not the matrix cores.  The 16-byte chunks of an LDS row are XOR-swizzled by the row
+// number so that fragment reads spread over all banks.
+//
+// The same kernel body serves three modes: the cosine score per layer (MODE 0), the same per KV
+// head with the minimum over heads (MODE 1), and the layer-mean Euclidean distance of the
+// paper's block-distance equation, for which a workgroup walks a group of layers (MODE 2).
 //
 // K and V are normalised by different norms but share one accumulator tile: after the K
 // phase the accumulators are multiplied by (aKq aKp)/(aVq aVp), the V phase continues into
