@@ -50,7 +50,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", type=int, default=2, help="1..5, the workloads of the benchmark definition")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (experiments only)")
-    ap.add_argument("--cpu-layers", type=int, default=2, help="layers the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-layers", type=int, default=8, help="layers the CPU oracle is timed on (0 = skip); 8 layers of the default workload are about 10 s")
     ap.add_argument("--layer-mean", type=int, default=1, help="also time the layer-mean distance entry point (0 = skip)")
     ap.add_argument("--pat-samples", type=int, default=1 << 22, help="warm-up sample size for the percentile threshold (0 = skip)")
     ap.add_argument("--admit", type=int, default=1, help="also time the admission of unmatched blocks into the pool (0 = skip)")
