@@ -147,7 +147,7 @@ size_t rc_remap_workspace_size(int32_t n_layers, int64_t R, int64_t E, int64_t Q
  *   refcount_in/out DEVICE int32 [L][NB]; refcount_out may be refcount_in
  *   freed           DEVICE uint8 [L][Q];  n_remapped: DEVICE int32 [L]
  *   workspace       DEVICE, >= rc_remap_workspace_size() bytes, 16-byte aligned
- * Only integer counts are accumulated: the result is the same on every run.  Q is limited to 8192.
+ * No atomics are used: the result is the same on every run.  Q is limited to 8192.
  */
 rc_status rc_remap_block_table(int32_t n_layers,
                                const int32_t* tables_in, int32_t* tables_out,

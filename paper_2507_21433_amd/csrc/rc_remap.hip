@@ -2,13 +2,13 @@
 // (ReasonCache Sec. IV-B: the kept block's reference count goes up, the table entry is
 // rewritten, nothing is copied; a block is freed only at reference count 0).
 //
-// Three stream-ordered launches.  The only atomics are integer adds into a workgroup's own LDS
-// histogram, whose sums do not depend on the order: the result is the same on every run.
+// Three stream-ordered launches, no atomics anywhere:
 //   1. scatter : slot_of[query_ids[q]] = q.  slot_of is never cleared: an entry s read for block b
 //                counts only if s < Q and query_ids[s] == b, so stale or uninitialised words are harmless
 //   2. gather  : table_out[e] = target of table_in[e] (16-byte loads and stores when the layout
 //                allows); references to matched query blocks are counted per workgroup in an LDS
-//                histogram, then stored as partials; the same workgroups copy their share of
+//                histogram that one wave at a time updates (equal keys inside a wave are merged
+//                with ballots), then stored as partials; the same workgroups copy their share of
 //                refcount_in to refcount_out
 //   3. finalize: per layer, cnt[q] = sum of partials; the query block loses cnt references,
 //                its target gains them.  Queries that share a target take turns through a
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kGatherThreads) void remap_gather_kernel(
     int32_t* __restrict__ partial, const int32_t* refcount_in, int32_t* refcount_out, long long rc_chunk,
     int rc_vec) {
   extern __shared__ int hist[];  // Q bins
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long l = blockIdx.y, g = blockIdx.x, G = gridDim.x;
   for (int q = tid; q < Q; q += kGatherThreads) hist[q] = 0;
   __syncthreads();
@@ -137,13 +137,30 @@ __global__ __launch_bounds__(kGatherThreads) void remap_gather_kernel(
         if (e < hi) tout[e] = outv[k];
       }
     }
-    // count the rewritten references: integer adds in LDS (whatever order the hardware takes them
-    // in, the counts are the same on every run)
+    // count the rewritten references, one wave at a time
+    bool any = false;
 #pragma unroll
-    for (int k = 0; k < kGatherPerThread; ++k)
-      if (slot[k] >= 0) atomicAdd(&hist[slot[k]], 1);
+    for (int k = 0; k < kGatherPerThread; ++k) any |= slot[k] >= 0;
+    if (__syncthreads_or(any)) {
+      for (int w = 0; w < kGatherThreads / 64; ++w) {
+        if (wave == w) {
+#pragma unroll
+          for (int k = 0; k < kGatherPerThread; ++k) {
+            const int s = slot[k];
+            unsigned long long active = __ballot(s >= 0);
+            while (active) {
+              const int leader = __ffsll((long long)active) - 1;
+              const int key = __shfl(s, leader);
+              const unsigned long long same = __ballot(s == key);
+              if (lane == leader) hist[key] += __popcll(same);
+              active &= ~same;
+            }
+          }
+        }
+        __syncthreads();
+      }
+    }
   }
-  __syncthreads();
   // this workgroup's share of the refcount copy (the finalize kernel then edits refcount_out)
   if (refcount_in != refcount_out) {
     const long long rlo = g * rc_chunk, rhi = (rlo + rc_chunk < NB) ? rlo + rc_chunk : NB;
