@@ -3,4 +3,4 @@
 ``binding`` holds the thin ctypes layer over the C-ABI HIP library; ``synth``
 draws the seeded synthetic workloads.  Nothing is loaded at import time.
 """
-__version__ = "0.1.0"
+__version__ = "0.2.0"

@@ -165,4 +165,4 @@ extern "C" rc_status rc_block_norms(const rc_kv_desc* desc, int32_t mode, const 
 
 extern "C" const char* rc_last_error(void) { return rc::error_buffer(); }
 
-extern "C" int32_t rc_version(void) { return 100; }
+extern "C" int32_t rc_version(void) { return 200; }  // 0.2.0: layer-mean distance, candidate lists, percentile threshold, admission
