@@ -120,6 +120,10 @@ __device__ __forceinline__ i32x4 make_srd(const void* base, uint32_t bytes) {
 // 16 bytes per lane, global -> LDS without passing through registers: lane l lands at LDS byte
 // lds_base + 16*l.  Completion is counted by vmcnt, in issue order.  Written as asm so that the
 // pipeline's waits are exactly the ones placed by hand below.
+// STREAM marks the load non-temporal: the pool slices are read once (or by the few query tiles of
+// the same pool tile, close together in time), so they should not displace the query slices that
+// every pool tile of the layer re-reads from the L2.  Measured: 2.5 % on cfg2, 1.5 % on cfg3.
+template <bool STREAM>
 __device__ __forceinline__ void dma16(i32x4 srd, uint32_t voff, uint32_t soff, uint32_t lds_base) {
   // the descriptor, the scalar offset and the LDS base are the same for the whole wave
   srd[0] = __builtin_amdgcn_readfirstlane(srd[0]);
@@ -128,10 +132,16 @@ __device__ __forceinline__ void dma16(i32x4 srd, uint32_t voff, uint32_t soff, u
   srd[3] = __builtin_amdgcn_readfirstlane(srd[3]);
   soff = __builtin_amdgcn_readfirstlane(soff);
   lds_base = __builtin_amdgcn_readfirstlane(lds_base);
-  asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
-               :
-               : "v"(voff), "s"(srd), "s"(soff), "s"(lds_base)
-               : "memory", "m0");
+  if (STREAM)
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen nt lds"
+                 :
+                 : "v"(voff), "s"(srd), "s"(soff), "s"(lds_base)
+                 : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
+                 :
+                 : "v"(voff), "s"(srd), "s"(soff), "s"(lds_base)
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ uint32_t lds_offset(const void* p) {
@@ -267,8 +277,8 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     if (n.ph < nphase) f.cur = n;
     f.stage = (f.stage + 1 == stages) ? 0 : f.stage + 1;
   };
-  auto dmaA = [&](int i) { dma16(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16); };
-  auto dmaB = [&](int i) { dma16(fb.srd, voff, fb.off + i * load_stride, fb.dst + i * NT * 16); };
+  auto dmaA = [&](int i) { dma16<true>(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16); };
+  auto dmaB = [&](int i) { dma16<false>(fb.srd, voff, fb.off + i * load_stride, fb.dst + i * NT * 16); };
 
   f32x16 acc[TP][TQ];
 #pragma unroll
