@@ -240,9 +240,10 @@ def assert_remap_equal(g, o):
 @pytest.mark.parametrize("in_place", [False, True])
 def test_remap_random(oracle, in_place):
     rng = np.random.RandomState(17)
-    for case in range(6):
+    for case in range(8):
         L, P, Q, R, E = [(3, 40, 12, 5, 30), (2, 3000, 700, 9, 1031), (1, 50, 1, 1, 7), (4, 10, 64, 3, 4099),
-                         (1, 5000, 2000, 64, 300), (2, 17, 9, 2, 1)][case]
+                         (1, 5000, 2000, 64, 300), (2, 17, 9, 2, 1), (2, 20000, 8192, 8, 5003),
+                         (1, 70000, 4500, 16, 4100)][case]
         say(f"remap random case {case} L={L} P={P} Q={Q} R={R} E={E} in_place={in_place}")
         NB = P + Q + 5
         ids = rng.permutation(NB)
