@@ -32,7 +32,9 @@
  * distance a hand-worked 3-4-5 example, a library norm routine, metric properties and the
  * expansion identity through the separately pinned norms and scores; for the percentile a
  * library quantile routine, hand cases and the defining inequalities of a quantile.
- * Every function here is pinned; none is "parity unpinned".
+ * Every function here is pinned; none is "parity unpinned".  tests/test_oracle_mutants.py
+ * compiles copies of this file with one planted mistake each and requires the pins to reject
+ * every copy.
  */
 #include <math.h>
 #include <stdint.h>

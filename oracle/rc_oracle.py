@@ -17,7 +17,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "rc_oracle.c")
-_LIB = os.path.join(_HERE, "librc_oracle.so")
+# RC_ORACLE_LIB names another build of the oracle to load instead (the tests use it to show that
+# the pins reject copies of rc_oracle.c with a planted mistake); such a library is never rebuilt here.
+_OVERRIDE = os.environ.get("RC_ORACLE_LIB")
+_LIB = _OVERRIDE or os.path.join(_HERE, "librc_oracle.so")
 
 F16, BF16 = 0, 1
 BLOCK, PER_HEAD_ALL = 0, 1
@@ -27,6 +30,8 @@ _lib = None
 
 def build(force=False):
     """Compile the oracle with gcc (plain -O2, OpenMP over independent blocks)."""
+    if _OVERRIDE:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
             ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]

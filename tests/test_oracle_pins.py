@@ -238,6 +238,12 @@ def test_match_vs_brute_force(oracle, dtype, mode):
     assert np.array_equal(r["match_idx"], want_match)
     assert r["match_idx"][1, 1] == 7 and r["best_score"][1, 1] == 1.0
     assert r["best_idx"][0, 1] != 7        # dead blocks are skipped, not merely rejected
+    # the pair-by-pair routine (used to sample full-size GPU results) must address layer, query and
+    # pool block the same way: every triple, in a shuffled order, against the brute-force matrix
+    li, qi, pi = [x.ravel().astype(np.int32) for x in np.meshgrid(np.arange(L), np.arange(Q), np.arange(P), indexing="ij")]
+    order = rng.permutation(li.size)
+    sp = oracle.score_pairs(dtype, mode, *a, li[order], qi[order], pi[order])
+    assert np.allclose(sp, S[li[order], qi[order], pi[order]], atol=1e-12, rtol=0)
 
 
 def test_tie_break_threshold_and_empty_pool(oracle):
@@ -366,6 +372,7 @@ def test_candidates_vs_exhaustive_and_brute_force(oracle, mode):
                     assert r["scores"][l, q, c] == -np.inf
     assert r["best_idx"][0, 0] == 5 and r["match_idx"][0, 0] == 5 and r["best_score"][0, 0] == 1.0
     assert r["best_idx"][1, 0] == 7                    # 5 is dead in layer 1
+    assert oracle.candidates(0, mode, *a, cand, live, 1.0)["match_idx"][0, 0] == 5      # inclusive threshold
     full = np.tile(np.arange(P, dtype=np.int32), (L, Q, 1))
     rf = oracle.candidates(0, mode, *a, full, live, 0.9)
     rm = oracle.match(0, mode, *a, live, 0.9)
@@ -655,5 +662,6 @@ def test_candidate_distances_vs_matrix_and_rules(oracle):
     # ties go to the lowest pool index whatever the order in the list
     kp2 = np.concatenate([kp[:, :1]] * 3, axis=1)
     vp2 = np.concatenate([vp[:, :1]] * 3, axis=1)
-    r = oracle.candidate_distances(0, kq, vq, kp2, vp2, np.tile(np.array([[2, 1, 0]], dtype=np.int32), (Q, 1)), None, 1e9)
-    assert (r["best_idx"] == 0).all()
+    for order in ([2, 1, 0], [1, 0, 2], [0, 2, 1]):
+        r = oracle.candidate_distances(0, kq, vq, kp2, vp2, np.tile(np.array([order], dtype=np.int32), (Q, 1)), None, 1e9)
+        assert (r["best_idx"] == 0).all(), order
