@@ -94,8 +94,10 @@ def test_layer_mean_duplicates_ties_dead(oracle):
             pr[n + "p"][:, 150] = pr[n + "p"][:, 7]
             pr[n + "p"][:, 20] = pr[n + "p"][:, 7]
             pr[n + "q"][:, 1] = 0                       # an all-zero query block
+            pr[n + "q"][:, 2] = pr[n + "p"][:, 33]      # the only copy of block 33, which is dead
     live = torch.ones(w.P, dtype=torch.uint8, device=DEV)
     live[7] = 0                                         # the original is dead: the lowest live copy (20) must win
+    live[33] = 0                                        # dead blocks are skipped by the search, not rejected after it
     pr, gpu, orc, rep = run_case(oracle, w, 0.5, live=live, tweak=tweak, tol_scale=1.0)
     tol = parity.dist_tol(w.T, w.H, w.Dh)
     assert orc["best_dist"][0] == 0.0 and gpu["best_dist"][0] <= tol and gpu["best_idx"][0] in (20, 150)
@@ -104,6 +106,7 @@ def test_layer_mean_duplicates_ties_dead(oracle):
     # identical pool blocks see the same instruction sequence, so their distances are bit-identical and the lowest wins
     assert gpu["best_idx"][0] == 20
     assert np.isfinite(gpu["best_dist"]).all() and (gpu["best_dist"] >= 0).all()
+    assert gpu["best_idx"][2] not in (-1, 33) and gpu["best_dist"][2] > 0.5 and gpu["match_idx"][2] == -1
 
 
 def test_layer_mean_empty_and_errors():
