@@ -66,6 +66,7 @@ struct MatchParams {
   int total;  // L * npt * nqt (layer-mean mode: groups * npt * nqt)
   int chunk;  // tiles handed to one XCD in a row
   int G;      // layer-mean mode: layers per group (one workgroup walks the layers of its group)
+  int S;      // split mode: workgroups per tile, each over its own part of the reduction (even)
   int stagger_wgs;   // workgroups of the first round (one per compute unit) ...
   int stagger_unit;  // ... start (tile % 16) * stagger_unit * 1024 clocks late
 };
@@ -157,7 +158,10 @@ struct Cursor {
 
 // BP x BQ tile of one layer.  MODE 0 = block score, 1 = per-head-all, 2 = layer-mean Euclidean
 // distance (the tile of a group of layers: the workgroup walks the layers one after the other and
-// adds |Kq-Kp| + |Vq-Vp| of every layer to the tile's running sum).
+// adds |Kq-Kp| + |Vq-Vp| of every layer to the tile's running sum), 3 = block score of a problem
+// with too few tiles to fill the chip: S workgroups share a tile, each takes 1/(S/2) of the K or of
+// the V reduction and stores its share of the scores, (aKq aKp <Kq,Kp>)/2 or (aVq aVp <Vq,Vp>)/2
+// over its elements, as a 256x256 tile of floats; a second kernel adds the S shares and selects.
 template <bool BF16, int BP, int BQ, int MODE>
 __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
@@ -172,7 +176,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   static_assert(NT >= BQ, "one thread per query column in the tile epilogue");
   static_assert(RING <= 160 * 1024, "ring fits the LDS of a compute unit");
   static_assert(sizeof(Part) * WP * BQ <= RING, "the epilogue scratch reuses the ring");
-  static_assert(MODE != 2 || (BP == 256 && BQ == 256 && WP == 2 && WQ == 2), "sum_index() decodes this tile shape");
+  static_assert((MODE != 2 && MODE != 3) || (BP == 256 && BQ == 256 && WP == 2 && WQ == 2), "sum_index() decodes this tile shape");
 
   __shared__ __attribute__((aligned(1024))) char s_ring[RING];
   const uint32_t ringA = lds_offset(s_ring), ringB = ringA + SA * A_STAGE;
@@ -183,9 +187,11 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   const int slot = wg >> 3;
   const int tile = ((slot / p.chunk) * 8 + (wg & 7)) * p.chunk + slot % p.chunk;
   if (tile >= p.total) return;
-  const int qt = tile % p.nqt;
-  const int pt = (tile / p.nqt) % p.npt;
-  const int lz = tile / (p.nqt * p.npt);  // layer, or group of layers in mode 2
+  const int split = (MODE == 3) ? tile % p.S : 0;   // which share of the tile's reduction
+  const int tile_id = (MODE == 3) ? tile / p.S : tile;
+  const int qt = tile_id % p.nqt;
+  const int pt = (tile_id / p.nqt) % p.npt;
+  const int lz = tile_id / (p.nqt * p.npt);  // layer, or group of layers in mode 2
   const int l_first = (MODE == 2) ? lz * p.G : lz;
   const int nl = (MODE == 2) ? min(p.G, p.L - l_first) : 1;
   int l = l_first;
@@ -245,16 +251,23 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // (MODE 1).  Step u of a phase reads 128 bytes per block at byte offset
   // head*256 + (u/2)*tok + (u%2)*128:  tok = 256 walks the flattened block, tok = H*256 walks
   // one head's [T][Dh] slice.
-  const int sps = (MODE != 1) ? (D / kBK) : (p.T * 2);
-  const int nphase = (MODE != 1) ? 2 : 2 * p.H;
+  // MODE 3: one phase of (D/kBK)/(S/2) steps, starting at step u_first of the K tensor (shares
+  // 0 .. S/2-1) or of the V tensor (the others).
+  const int sps = (MODE == 3) ? (D / kBK) / (p.S / 2) : (MODE != 1) ? (D / kBK) : (p.T * 2);
+  const int nphase = (MODE == 3) ? 1 : (MODE != 1) ? 2 : 2 * p.H;
   const int tok = (MODE != 1) ? 256 : p.H * 256;
+  const bool split_v = (MODE == 3) && split >= p.S / 2;
+  const int u_first = (MODE == 3) ? (split % (p.S / 2)) * sps : 0;
   auto advance = [&](Cursor& c) {
     if (++c.u == sps) {
       c.u = 0;
       ++c.ph;
     }
   };
-  auto byte_off = [&](const Cursor& c) { return (uint32_t)((c.ph >> 1) * 256 + (c.u >> 1) * tok + (c.u & 1) * 128); };
+  auto byte_off = [&](const Cursor& c) {
+    if (MODE == 3) return (uint32_t)((c.u + u_first) * 128);
+    return (uint32_t)((c.ph >> 1) * 256 + (c.u >> 1) * tok + (c.u & 1) * 128);
+  };
 
   // Where the next pool / query slice comes from and which ring stage it goes to.  Past the last
   // step the cursor stays on the last slice: the two refills that nobody needs re-read valid
@@ -267,7 +280,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   };
   Feed fa{{0, 0}, 0, srdAk, 0, 0}, fb{{0, 0}, 0, srdBk, 0, 0};
   auto prepare = [&](Feed& f, const i32x4& k_srd, const i32x4& v_srd, uint32_t ring, int stage_bytes) {
-    f.srd = (f.cur.ph & 1) ? v_srd : k_srd;
+    f.srd = ((MODE == 3) ? split_v : (f.cur.ph & 1) != 0) ? v_srd : k_srd;
     f.off = byte_off(f.cur);
     f.dst = ring + f.stage * stage_bytes + wave * 1024;
   };
@@ -559,6 +572,8 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
       run_phase();
       finish_head(h);
     }
+  } else if (MODE == 3) {
+    run_phase();
   } else {
     for (int li = 0;;) {
       run_phase();
@@ -584,6 +599,35 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus refills of the last steps have landed
 
   if (MODE == 2) return;  // the sums of this group's layers are in place, tile by tile in register order
+
+  if (MODE == 3) {
+    // this share of the tile's scores, in register order like the sums of the layer-mean mode:
+    // shares are laid out [layer][share][pool tile][query tile]
+    float rq[TQ], fq[TQ];
+    query_scales(0, rq, fq);
+    const long long tile_lin = (((long long)lz * p.S + split) * p.npt + pt) * p.nqt + qt;
+    f32x4* out = reinterpret_cast<f32x4*>(p.dpart) + tile_lin * (BP * BQ / 4) + (long long)wave * (TP * 4 * TQ * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < TP; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 rp, fp;
+        pool_scales(row_of(i, g), 0, rp, fp);
+#pragma unroll
+        for (int j = 0; j < TQ; ++j) {
+          f32x4 d;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            // fq fp = aVq aVp / 2; rq rp = (aKq aKp) / (aVq aVp)
+            const float f = split_v ? fq[j] * fp[e] : (rq[j] * fq[j]) * (rp[e] * fp[e]);
+            d[e] = acc[i][j][4 * g + e] * f;
+          }
+          out[((i * 4 + g) * TQ + j) * 64] = d;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    return;
+  }
 
   // ---- tile epilogue: scores, dead/tail masking, top-2 per query column
   float best[TQ], second[TQ];
@@ -690,20 +734,25 @@ __device__ __forceinline__ int sum_index(int r, int c) {
   return ((((wave * 4 + i) * 4 + g) * 4 + j) * 64 + lane) * 4;
 }
 
-// Layer-mean mode, selection: nearest live pool block per query from the sums (one 256x256 tile
-// after the other per group, each in the tile kernel's register order).
-// grid = (query tiles of 64, pool chunks of sel_rows rows, sel_rows a multiple of 16); a thread
-// owns one query column and every fourth group of four rows.  Works on -distance so that "higher
-// wins, equal goes to the lower index" is the same rule as for scores.
-__global__ __launch_bounds__(256) void layer_mean_select_kernel(const float* __restrict__ dpart, int groups, int P,
-                                                                int Q, int npt, int nqt, int sel_rows, float scale,
-                                                                const uint8_t* __restrict__ live,
-                                                                Part* __restrict__ part) {
+// Selection from tiles of sums (one 256x256 tile after the other per group, each in the tile
+// kernel's register order): the value of a pair is -scale times the sum of its element over the
+// groups.  Layer-mean mode: groups = groups of layers, scale = 1/(2dhN), so "higher wins, equal
+// goes to the lower index" on -distance picks the nearest live pool block.  Split mode: groups =
+// the shares of a tile's reduction, scale = -1, the value is the score; blockIdx.z is the layer.
+// grid = (query tiles of 64, pool chunks of sel_rows rows, layers); sel_rows is a multiple of 16;
+// a thread owns one query column and every fourth group of four rows.
+__global__ __launch_bounds__(256) void tile_sums_select_kernel(const float* __restrict__ dpart, int groups, int P,
+                                                               int Q, int npt, int nqt, int sel_rows, float scale,
+                                                               const uint8_t* __restrict__ live,
+                                                               Part* __restrict__ part) {
   __shared__ Part s_part[4][64];
   const int tq = threadIdx.x & 63, tp = threadIdx.x >> 6;
   const int q = blockIdx.x * 64 + tq;
   const int pbeg = blockIdx.y * sel_rows, pend = min(P, pbeg + sel_rows);
   const long long gstride = (long long)npt * nqt * 65536;
+  dpart += (long long)blockIdx.z * groups * gstride;
+  if (live) live += (long long)blockIdx.z * P;
+  part += (long long)blockIdx.z * gridDim.y * Q;
   float best = -INFINITY, second = -INFINITY;
   int bidx = -1;
   if (q < Q) {
@@ -841,6 +890,64 @@ inline size_t layer_mean_part_offset(int groups, int64_t npt, int64_t nqt) {
   return (size_t)groups * (size_t)npt * (size_t)nqt * 65536 * sizeof(float);
 }
 
+// A tile kernel launch runs in rounds of one workgroup per compute unit, and a problem with few
+// tiles (a call for one layer, a small pool) leaves most of the chip idle or pays a whole round
+// for a few left-over tiles.  Such problems split the reduction of every tile over S workgroups
+// (S even: half of them on the K tensor, half on V).  S is the power of two with the lowest
+// estimated time, in units of one pipeline step:
+//   rounds(S) * (steps of a share + 6 for filling the pipeline and storing the share)
+//   + 0.03 per tile share for the pass that adds the shares + 5 for its launch,
+// and the split is used when that is at least 10 % below the estimate for whole tiles.  The
+// constants come from measurements of 1 to 144 tiles of the 256 x 256 shape (within 10 % from 64
+// tiles up; a single layer of 16 tiles takes 143 us against 112 estimated).  A share has at least
+// 8 steps; the shares of all tiles take at most 512 MB; problems of more than one round are left
+// alone.  With at most 128 query blocks the whole-tile
+// path has its narrow tiles, so the split is only used below half a round there.  Block mode only.
+// The decision depends on the shape alone (an MI355X has 256 compute units), so that the workspace
+// size does not depend on the device that happens to be current.
+constexpr int kSplitComputeUnits = 256;
+inline int split_count(int mode, int64_t L, int64_t P, int64_t Q, int T, int H) {
+  if (mode != RC_SCORE_BLOCK || P <= 0 || Q <= 0 || L <= 0) return 1;
+  const int64_t tiles = L * ((P + 255) / 256) * ((Q + 255) / 256);
+  if (tiles > kSplitComputeUnits) return 1;  // more than one round: measured gains of 0-6 % only (workgroups of
+                                             // later rounds start as earlier ones end, the rounds are not that rigid)
+  if (Q <= 128 && tiles * 2 > kSplitComputeUnits) return 1;
+  const int steps = T * H * 128 / kBK;  // per tensor
+  auto estimate = [&](int S) {
+    const double rounds = (double)((tiles * S + kSplitComputeUnits - 1) / kSplitComputeUnits);
+    return rounds * (2.0 * steps / S + 6.0) + (S > 1 ? 0.03 * (double)(tiles * S) + 5.0 : 0.0);
+  };
+  int best = 1;
+  double best_cost = 0.9 * estimate(1);
+  for (int S = 2; tiles * S <= 2048 && 2 * steps / S >= 8 && steps % (S / 2) == 0; S *= 2) {
+    const double c = estimate(S);
+    if (c < best_cost) {
+      best_cost = c;
+      best = S;
+    }
+  }
+  return best;
+}
+
+struct SplitLayout {
+  int S;
+  int64_t npt, nqt;
+  int sel_rows;
+  int64_t nchunks;
+  size_t part_offset, bytes;
+};
+inline SplitLayout split_layout(int S, int64_t L, int64_t P, int64_t Q) {
+  SplitLayout r;
+  r.S = S;
+  r.npt = (P + 255) / 256;
+  r.nqt = (Q + 255) / 256;
+  r.sel_rows = select_rows(P, Q);
+  r.nchunks = (P + r.sel_rows - 1) / r.sel_rows;
+  r.part_offset = (size_t)L * (size_t)S * (size_t)r.npt * (size_t)r.nqt * 65536 * sizeof(float);
+  r.bytes = r.part_offset + (size_t)L * (size_t)r.nchunks * (size_t)Q * sizeof(Part);
+  return r;
+}
+
 template <bool BF16>
 void launch_tiles(int mode, const MatchParams& mp, unsigned grid, hipStream_t st) {
   if (mode == RC_SCORE_BLOCK && mp.Q <= kNarrowTile.bq)
@@ -860,6 +967,8 @@ extern "C" size_t rc_match_workspace_size(const rc_kv_desc* qdesc, int32_t mode,
   using namespace rc;
   if (!qdesc || Q < 0 || P < 0 || qdesc->n_layers < 0) return 0;
   if (mode != RC_SCORE_BLOCK && mode != RC_SCORE_PER_HEAD_ALL) return 0;
+  const int S = split_count(mode, qdesc->n_layers, P, Q, qdesc->block_tokens, qdesc->n_kv_heads);
+  if (S > 1) return split_layout(S, qdesc->n_layers, P, Q).bytes;
   const TileShape ts = tile_for(mode, Q);
   const int64_t npt = (P + ts.bp - 1) / ts.bp;
   const int64_t n = (int64_t)qdesc->n_layers * (npt > 0 ? npt : 1) * Q;
@@ -899,6 +1008,55 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     return fail(RC_ERR_WORKSPACE, "rc_match_blocks: workspace of %zu bytes needed (16-byte aligned), got %zu", need,
                 workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int S = split_count(mode, L, P, Q, qdesc->block_tokens, qdesc->n_kv_heads);
+  const long long LQ = (long long)L * Q;
+
+  if (S > 1) {
+    // few tiles: shares of every tile's reduction, then sum + selection, then the merge over pool chunks
+    const SplitLayout sl = split_layout(S, L, P, Q);
+    MatchParams mp;
+    mp.kq = static_cast<const char*>(kq);
+    mp.vq = static_cast<const char*>(vq);
+    mp.kp = static_cast<const char*>(kp);
+    mp.vp = static_cast<const char*>(vp);
+    mp.q_ksq = q_ksq;
+    mp.q_vsq = q_vsq;
+    mp.p_ksq = p_ksq;
+    mp.p_vsq = p_vsq;
+    mp.live = pool_live;
+    mp.part = nullptr;
+    mp.dpart = static_cast<float*>(workspace);
+    mp.q_lstride_b = qdesc->layer_stride * 2;
+    mp.p_lstride_b = pdesc->layer_stride * 2;
+    mp.L = L;
+    mp.Q = (int)Q;
+    mp.P = (int)P;
+    mp.T = qdesc->block_tokens;
+    mp.H = qdesc->n_kv_heads;
+    mp.npt = (int)sl.npt;
+    mp.nqt = (int)sl.nqt;
+    mp.total = (int)(L * sl.npt * sl.nqt * S);
+    mp.chunk = 32;
+    mp.G = 1;
+    mp.S = S;
+    mp.stagger_wgs = 0;
+    mp.stagger_unit = 0;
+    const int64_t per_round = 8LL * mp.chunk;
+    const unsigned grid = (unsigned)(((mp.total + per_round - 1) / per_round) * per_round);
+    if (qdesc->dtype == RC_BF16)
+      match_tile_kernel<true, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
+    else
+      match_tile_kernel<false, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
+    if (rc_status s = check_launch("rc_match_blocks(tile shares)")) return s;
+    Part* part = reinterpret_cast<Part*>(static_cast<char*>(workspace) + sl.part_offset);
+    const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)sl.nchunks, (unsigned)L);
+    tile_sums_select_kernel<<<sgrid, 256, 0, st>>>(mp.dpart, S, (int)P, (int)Q, (int)sl.npt, (int)sl.nqt, sl.sel_rows,
+                                                   -1.0f, pool_live, part);
+    if (rc_status s = check_launch("rc_match_blocks(select)")) return s;
+    match_finalize_kernel<<<(unsigned)((LQ + 255) / 256), 256, 0, st>>>(part, (int)sl.nchunks, LQ, (int)Q, tau, best_idx,
+                                                                       best_score, match_idx, second_score);
+    return check_launch("rc_match_blocks(finalize)");
+  }
 
   if (P > 0) {
     MatchParams mp;
@@ -925,6 +1083,7 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.chunk = 32;
     mp.dpart = nullptr;
     mp.G = 1;
+    mp.S = 1;
     mp.stagger_wgs = compute_units();
     mp.stagger_unit = kStaggerUnit;
     const int64_t per_round = 8LL * mp.chunk;
@@ -935,7 +1094,6 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
       launch_tiles<false>(mode, mp, grid, st);
     if (rc_status s = check_launch("rc_match_blocks(tiles)")) return s;
   }
-  const long long LQ = (long long)L * Q;
   match_finalize_kernel<<<(unsigned)((LQ + 255) / 256), 256, 0, st>>>(static_cast<const Part*>(workspace), (int)npt, LQ,
                                                                      (int)Q, tau, best_idx, best_score, match_idx,
                                                                      second_score);
@@ -1016,6 +1174,7 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     mp.total = (int)total;
     mp.chunk = 32;
     mp.G = ls.G;
+    mp.S = 1;
     mp.stagger_wgs = compute_units();
     mp.stagger_unit = kStaggerUnit;
     const int64_t per_round = 8LL * mp.chunk;
@@ -1027,7 +1186,7 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     if (rc_status s = check_launch("rc_match_blocks_layer_mean(tiles)")) return s;
     const float scale = 1.0f / ((float)L * 2.0f * (float)qdesc->block_tokens * (float)qdesc->n_kv_heads);
     const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)nchunks);
-    layer_mean_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, (int)npt, (int)nqt, sel_rows, scale,
+    tile_sums_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, (int)npt, (int)nqt, sel_rows, scale,
                                                     pool_live, part);
     if (rc_status s = check_launch("rc_match_blocks_layer_mean(select)")) return s;
   }

@@ -67,10 +67,15 @@ def test_match_validation(lib):
     q, p = desc(n=4), desc(n=64)
     args = lambda **kw: [kw.get("qd", ctypes.byref(q)), kw.get("pd", ctypes.byref(p)), kw.get("mode", 0),
                          kw.get("kq", FAKE), FAKE, kw.get("Q", 4), FAKE, FAKE, FAKE, FAKE, kw.get("P", 64), FAKE, FAKE,
-                         None, kw.get("tau", 0.9), FAKE, FAKE, FAKE, None, kw.get("ws", FAKE), kw.get("wsb", 1 << 20),
+                         None, kw.get("tau", 0.9), FAKE, FAKE, FAKE, None, kw.get("ws", FAKE), kw.get("wsb", 1 << 26),
                          None]
-    assert lib.rc_match_workspace_size(ctypes.byref(q), 0, 4, 64) == 2 * 1 * 4 * 16
-    assert lib.rc_match_workspace_size(ctypes.byref(q), 0, 4, 257) == 2 * 2 * 4 * 16
+    # per-head mode, and block mode with more than 128 tiles: one 16-byte partial per (layer, pool tile, query)
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 64) == 2 * 1 * 4 * 16
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 257) == 2 * 2 * 4 * 16
+    many = desc(L=200, n=4)
+    assert lib.rc_match_workspace_size(ctypes.byref(many), 0, 4, 257) == 200 * 2 * 4 * 16
+    # block mode with few tiles: 2 tiles x 64 shares of 256 KB, then 2 pool chunks of partials per layer
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 0, 4, 64) == 2 * 64 * 65536 * 4 + 2 * 2 * 4 * 16
     assert lib.rc_match_workspace_size(ctypes.byref(q), 9, 4, 64) == 0
     assert lib.rc_match_blocks(*args(Q=0)) == 0                      # nothing to do
     assert lib.rc_match_blocks(*args(wsb=8)) == 3

@@ -109,6 +109,39 @@ def test_match_ragged_tiles(oracle, dtype, P, Q):
         assert abs(gpu["best_score"][1, 0] - 1.0) < 1e-5 and abs(gpu["second_score"][1, 0] - 1.0) < 1e-5
 
 
+@pytest.mark.parametrize("L,P,Q", [(48, 513, 257), (80, 700, 64), (70, 513, 128)])
+def test_match_many_layers_whole_tiles(oracle, L, P, Q):
+    # more than 128 tiles: every tile is computed by one workgroup (no split of the reduction), with the
+    # 256-, 64- and 128-column tile; the small cases above all take the split path
+    w = synth.scaled(synth.WORKLOADS[2], name=f"whole_tiles_L{L}_{P}x{Q}", L=L, P=P, Q=Q, planted_frac=0.3, R=1,
+                     E=P + Q, seed=13)
+    say(w.name)
+    pr = synth.make_problem(w, DEV)
+    live = pr["live"].clone()
+    live[:, 5] = 0
+    live[0, int(pr["plan"].planted_targets[0])] = 0
+    pr["kp"][:, P - 2] = pr["kp"][:, 1]       # bit-identical pool blocks in different tiles: lowest index must win
+    pr["vp"][:, P - 2] = pr["vp"][:, 1]
+    pr["kq"][:, 0] = pr["kp"][:, 1]
+    pr["vq"][:, 0] = pr["vp"][:, 1]
+    gpu, orc, rep = full_check(oracle, w, pr, live)
+    assert (gpu["best_idx"][:, 0] == 1).all() and (gpu["match_idx"][:, 0] == 1).all()
+
+
+def test_match_split_shapes(oracle):
+    # the split of the reduction at its extremes: one tile over 64 shares (8 steps each), 128 tiles over 2
+    # shares (a whole tensor each), head counts whose step count is not a power of two
+    for (L, P, Q, T, H) in [(1, 200, 30, 16, 8), (32, 1000, 40, 16, 8), (1, 300, 257, 16, 3), (2, 257, 5, 32, 5),
+                            (1, 100, 7, 16, 1)]:
+        w = synth.scaled(synth.WORKLOADS[2], name=f"split_L{L}_{P}x{Q}_T{T}_H{H}", L=L, P=P, Q=Q, T=T, H=H,
+                         planted_frac=0.3, R=1, E=P + Q, seed=19)
+        say(w.name)
+        pr = synth.make_problem(w, DEV)
+        live = pr["live"].clone()
+        live[:, 3] = 0
+        full_check(oracle, w, pr, live)
+
+
 def test_match_degenerate_blocks(oracle):
     # zero query, zero pool block, zero V only, huge and tiny norms, tau = 1 on exact duplicates
     w = synth.scaled(synth.WORKLOADS[2], name="degenerate", L=1, P=300, Q=40, planted_frac=0.0, R=1, E=340, seed=5,
