@@ -172,6 +172,27 @@ def main():
             "hbm_frac": L * P * w.block_bytes / (pool_norm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "rc_remap_block_table": {"ms": remap_ms, "gb_per_s": remap_bytes / (remap_ms * 1e-3) / 1e9},
     }
+    if L > 1 and P > 0:
+        # the same search called for one layer at a time, as an engine that scores a layer when its KV is written
+        # would call it: few tiles, so block mode splits every tile's reduction over several workgroups
+        one = [pr[n][:1] for n in ("kq", "vq", "kp", "vp")]
+        qk1, qv1, pk1, pv1 = qk[:1], qv[:1], pk[:1], pv[:1]
+        live1 = pr["live"][:1]
+        ws1 = torch.empty(rc.rc_match_workspace_size(one[0], w.mode, Q, P), dtype=torch.uint8, device=dev)
+        out1 = {k: torch.empty_like(v[:1]) for k, v in out.items()}
+        call1 = lambda: rc.rc_match_blocks(one[0], one[1], qk1, qv1, one[2], one[3], pk1, pv1, live1, w.tau, w.mode,
+                                           workspace=ws1, out=out1)
+        call1()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            call1()
+        e1.record()
+        torch.cuda.synchronize()
+        one_ms = e0.elapsed_time(e1) / args.steps
+        kernels["rc_match_blocks(one layer per call, not in the step)"] = {
+            "ms": one_ms, "tflops": flop / L / (one_ms * 1e-3) / 1e12, "workspace_bytes": ws1.numel()}
+        del ws1
     if args.candidates > 0 and P > 0:
         # candidate-restricted Stage 2 (not part of the step): C random pool blocks per query, timed the same way
         C = args.candidates
