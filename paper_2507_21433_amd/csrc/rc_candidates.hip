@@ -47,12 +47,17 @@ struct CandParams {
 // chunk a thread holds is used against all of them, which divides the query traffic from the L2.
 // Thread t takes the 16-byte chunks t, t+256, ...; 16 consecutive chunks are one head of one
 // token, so with 16*heads dividing 256 a thread stays in one head: head = (t/16) % heads.
+// ANYH (per-head mode with a head count that does not divide 16, e.g. 10 KV heads): the head of a
+// thread's chunk changes from one trip to the next, so every trip ends with the sum over the 16
+// lanes of a (token, head) group, added by the group's first lane to its own slot
+// hpart[candidate][K or V][head][group]: no two groups share a slot, so plain LDS updates do.
 constexpr int kCandPerWg = 16;
 
-template <bool BF16>
+template <bool BF16, bool ANYH>
 __global__ __launch_bounds__(kCandThreads) void candidates_kernel(const CandParams p) {
   __shared__ float part[kCandPerWg][2][kCandThreads / 16];
   __shared__ float head_score[kCandPerWg][16];
+  __shared__ float hpart[ANYH ? kCandPerWg : 1][2][ANYH ? 16 : 1][ANYH ? kCandThreads / 16 : 1];
   const int c0 = blockIdx.x * kCandPerWg, q = blockIdx.y, tid = threadIdx.x;
   const long long l = blockIdx.z;
   const long long slot0 = (l * p.Q + q) * p.C + c0;
@@ -72,14 +77,18 @@ __global__ __launch_bounds__(kCandThreads) void candidates_kernel(const CandPara
     if (!valid[c] && tid == 0 && c0 + c < p.C) p.scores[slot0 + c] = -INFINITY;
   }
   if (!any) return;
+  if (ANYH) {
+    float* z = &hpart[0][0][0][0];
+    for (int i = tid; i < kCandPerWg * 2 * 16 * (kCandThreads / 16); i += kCandThreads) z[i] = 0.f;
+    __syncthreads();
+  }
   const u32x4* xq_k = reinterpret_cast<const u32x4*>(p.kq + l * p.q_lstride_b + (long long)q * p.block_bytes);
   const u32x4* xq_v = reinterpret_cast<const u32x4*>(p.vq + l * p.q_lstride_b + (long long)q * p.block_bytes);
   const int chunks = p.block_bytes / 16;
   float dk[kCandPerWg], dv[kCandPerWg];
 #pragma unroll
   for (int c = 0; c < kCandPerWg; ++c) dk[c] = dv[c] = 0.f;
-#pragma unroll 2
-  for (int i = tid; i < chunks; i += kCandThreads) {  // chunks = 16*T*H is a multiple of 256
+  auto trip = [&](int i) {
     const u32x4 qk = xq_k[i], qv = xq_v[i];
     u32x4 pk[kCandPerWg], pv[kCandPerWg];
 #pragma unroll
@@ -94,6 +103,31 @@ __global__ __launch_bounds__(kCandThreads) void candidates_kernel(const CandPara
         dk[c] = dot8<BF16>(qk, pk[c], dk[c]);
         dv[c] = dot8<BF16>(qv, pv[c], dv[c]);
       }
+    if (ANYH) {
+      const int head = (i >> 4) % p.heads;
+#pragma unroll
+      for (int c = 0; c < kCandPerWg; ++c)
+        if (valid[c]) {  // the same for the whole workgroup
+#pragma unroll
+          for (int off = 8; off > 0; off >>= 1) {
+            dk[c] += __shfl_xor(dk[c], off);
+            dv[c] += __shfl_xor(dv[c], off);
+          }
+          if ((tid & 15) == 0) {
+            hpart[c][0][head][tid >> 4] += dk[c];
+            hpart[c][1][head][tid >> 4] += dv[c];
+          }
+          dk[c] = dv[c] = 0.f;
+        }
+    }
+  
+  };
+  // chunks = 16*T*H is a multiple of 256
+  if (ANYH) {
+    for (int i = tid; i < chunks; i += kCandThreads) trip(i);
+  } else {
+#pragma unroll 2
+    for (int i = tid; i < chunks; i += kCandThreads) trip(i);
   }
   // sum over the 16 lanes that share a (token, head) group, then over the groups of a head
 #pragma unroll
@@ -112,9 +146,16 @@ __global__ __launch_bounds__(kCandThreads) void candidates_kernel(const CandPara
   const int c = tid >> 4, h = tid & 15;  // one thread per (candidate, head)
   if (c < kCandPerWg && h < p.heads && valid[c]) {
     float sk = 0.f, sv = 0.f;
-    for (int g = h; g < kCandThreads / 16; g += p.heads) {
-      sk += part[c][0][g];
-      sv += part[c][1][g];
+    if (ANYH) {
+      for (int g = 0; g < kCandThreads / 16; ++g) {
+        sk += hpart[c][0][h][g];
+        sv += hpart[c][1][h][g];
+      }
+    } else {
+      for (int g = h; g < kCandThreads / 16; g += p.heads) {
+        sk += part[c][0][g];
+        sv += part[c][1][g];
+      }
     }
     const long long oq = (l * p.Q + q) * p.heads + h, op = (l * p.P + pidx[c]) * p.heads + h;
     const float nkq = p.q_ksq[oq], nvq = p.q_vsq[oq], nkp = p.p_ksq[op], nvp = p.p_vsq[op];
@@ -331,8 +372,6 @@ extern "C" rc_status rc_score_candidates(const rc_kv_desc* qdesc, const rc_kv_de
   if (C < 0) return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: negative C");
   if (!(tau == tau)) return fail(RC_ERR_INVALID_ARG, "rc_score_candidates: tau is NaN");
   const int H = qdesc->n_kv_heads;
-  if (mode == RC_SCORE_PER_HEAD_ALL && (16 % H) != 0)
-    return fail(RC_ERR_UNSUPPORTED, "rc_score_candidates: per-head mode needs n_kv_heads in {1,2,4,8,16}, got %d", H);
   const int L = qdesc->n_layers;
   if (L == 0 || Q == 0) return RC_OK;
   if (!kq || !vq || !q_ksq || !q_vsq || !best_idx || !best_score || !match_idx)
@@ -366,10 +405,18 @@ extern "C" rc_status rc_score_candidates(const rc_kv_desc* qdesc, const rc_kv_de
     cp.block_bytes = qdesc->block_tokens * H * qdesc->head_dim * 2;  // T >= 16, Dh = 128: a multiple of 16 KB / 4
     cp.heads = (mode == RC_SCORE_BLOCK) ? 1 : H;
     const dim3 grid((unsigned)((C + kCandPerWg - 1) / kCandPerWg), (unsigned)Q, (unsigned)L);
-    if (qdesc->dtype == RC_BF16)
-      candidates_kernel<true><<<grid, kCandThreads, 0, st>>>(cp);
-    else
-      candidates_kernel<false><<<grid, kCandThreads, 0, st>>>(cp);
+    const bool any_h = mode == RC_SCORE_PER_HEAD_ALL && (16 % H) != 0;  // a thread's chunks wander over the heads
+    if (qdesc->dtype == RC_BF16) {
+      if (any_h)
+        candidates_kernel<true, true><<<grid, kCandThreads, 0, st>>>(cp);
+      else
+        candidates_kernel<true, false><<<grid, kCandThreads, 0, st>>>(cp);
+    } else {
+      if (any_h)
+        candidates_kernel<false, true><<<grid, kCandThreads, 0, st>>>(cp);
+      else
+        candidates_kernel<false, false><<<grid, kCandThreads, 0, st>>>(cp);
+    }
     if (rc_status s = check_launch("rc_score_candidates(score)")) return s;
   }
   const long long LQ = (long long)L * Q;

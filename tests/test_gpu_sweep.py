@@ -62,22 +62,21 @@ def test_random_shape(oracle, case):
                       pr["refcount"].cpu().numpy())
     for k in ("tables", "refcount", "freed", "n_remapped"):
         assert np.array_equal(r[k].cpu().numpy(), ro[k]), k
-    # candidate lists (per-head lists need a head count that divides 16)
-    if w.mode == 0 or 16 % w.H == 0:
-        rng = np.random.RandomState(case)
-        C = int(rng.randint(1, 20))
-        cand = rng.randint(-1, w.P, size=(w.L, w.Q, C)).astype(np.int32)
-        c = rc.rc_score_candidates(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, live,
-                                   torch.as_tensor(cand, device=DEV), w.tau, w.mode)
-        torch.cuda.synchronize()
-        co = oracle.candidates(d, w.mode, *bits, cand, live.cpu().numpy(), w.tau)
-        cs = c["scores"].cpu().numpy().astype(np.float64)
-        fin = np.isfinite(co["scores"])
-        assert np.array_equal(np.isfinite(cs), fin)
-        assert not fin.any() or np.abs(cs[fin] - co["scores"][fin]).max() <= 2e-5
-        # the exhaustive search and the list agree on every listed pair
-        ll, qq, cc = np.nonzero(fin)
-        assert np.abs(o["scores"][ll, qq, cand[ll, qq, cc]] - co["scores"][ll, qq, cc]).max(initial=0.0) <= 1e-12
+    # candidate lists
+    rng = np.random.RandomState(case)
+    C = int(rng.randint(1, 20))
+    cand = rng.randint(-1, w.P, size=(w.L, w.Q, C)).astype(np.int32)
+    c = rc.rc_score_candidates(pr["kq"], pr["vq"], qk, qv, pr["kp"], pr["vp"], pk, pv, live,
+                               torch.as_tensor(cand, device=DEV), w.tau, w.mode)
+    torch.cuda.synchronize()
+    co = oracle.candidates(d, w.mode, *bits, cand, live.cpu().numpy(), w.tau)
+    cs = c["scores"].cpu().numpy().astype(np.float64)
+    fin = np.isfinite(co["scores"])
+    assert np.array_equal(np.isfinite(cs), fin)
+    assert not fin.any() or np.abs(cs[fin] - co["scores"][fin]).max() <= 2e-5
+    # the exhaustive search and the list agree on every listed pair
+    ll, qq, cc = np.nonzero(fin)
+    assert np.abs(o["scores"][ll, qq, cand[ll, qq, cc]] - co["scores"][ll, qq, cc]).max(initial=0.0) <= 1e-12
     # the paper's layer-mean distance (block mode norms)
     if w.mode == 0:
         lv = live.min(dim=0).values.contiguous()
