@@ -175,8 +175,7 @@ rc_status rc_remap_block_table(int32_t n_layers,
  *   best_idx        DEVICE int32 [L][Q]: candidate with the highest score, equal scores to
  *                   the lowest pool index; -1 if the list has no valid entry
  *   best_score      DEVICE float [L][Q] (-inf if none);  match_idx: best_idx if >= tau else -1
- * Everything else as in rc_match_blocks.  RC_SCORE_PER_HEAD_ALL needs n_kv_heads in
- * {1, 2, 4, 8, 16}.  C == 0 writes -1 / -inf.
+ * Everything else as in rc_match_blocks.  C == 0 writes -1 / -inf.
  */
 rc_status rc_score_candidates(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_t mode,
                               const void* kq, const void* vq, int64_t Q,
