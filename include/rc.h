@@ -78,10 +78,11 @@ rc_status rc_block_norms(const rc_kv_desc* desc, int32_t mode,
                          float* k_sqnorm, float* v_sqnorm, void* hip_stream);
 
 /* Bytes of DEVICE workspace rc_match_blocks needs for this problem (0 on bad arguments).
- * 16 bytes per (layer, pool tile of 256 blocks, query block).  A block-mode problem of at most 256
- * tiles of 256 x 256 blocks (one layer at a time, a small pool) may instead be computed as several
- * shares per tile and then needs up to 512 MB: 256 KB per share plus the 16-byte partials.  The
- * size depends on the arguments only, not on the current device. */
+ * 16 bytes per (layer, pool tile of 256 blocks, query block).  A problem of at most 256 tiles of
+ * 256 x 256 blocks (one layer at a time, a small pool) may instead be computed as several shares
+ * per tile (parts of the reduction, or heads in per-head mode) and then needs up to 512 MB: 256 KB
+ * per share plus the 16-byte partials.  The size depends on the arguments only, not on the
+ * current device. */
 size_t rc_match_workspace_size(const rc_kv_desc* qdesc, int32_t mode, int64_t Q, int64_t P);
 
 /*

@@ -162,6 +162,8 @@ struct Cursor {
 // with too few tiles to fill the chip: S workgroups share a tile, each takes 1/(S/2) of the K or of
 // the V reduction and stores its share of the scores, (aKq aKp <Kq,Kp>)/2 or (aVq aVp <Vq,Vp>)/2
 // over its elements, as a 256x256 tile of floats; a second kernel adds the S shares and selects.
+// MODE 4 = the same for the per-head-all score: S = H shares, share h computes the score of head h
+// over the head's K and V slices, and the second kernel takes the minimum over the shares.
 template <bool BF16, int BP, int BQ, int MODE>
 __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
@@ -176,7 +178,9 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   static_assert(NT >= BQ, "one thread per query column in the tile epilogue");
   static_assert(RING <= 160 * 1024, "ring fits the LDS of a compute unit");
   static_assert(sizeof(Part) * WP * BQ <= RING, "the epilogue scratch reuses the ring");
-  static_assert((MODE != 2 && MODE != 3) || (BP == 256 && BQ == 256 && WP == 2 && WQ == 2), "sum_index() decodes this tile shape");
+  static_assert(MODE < 2 || (BP == 256 && BQ == 256 && WP == 2 && WQ == 2), "sum_index() decodes this tile shape");
+  constexpr bool SHARES = (MODE == 3 || MODE == 4);    // several workgroups per tile, results stored as tiles of floats
+  constexpr bool PER_HEAD = (MODE == 1 || MODE == 4);  // phases are heads' [T][Dh] slices, norms are per head
 
   __shared__ __attribute__((aligned(1024))) char s_ring[RING];
   const uint32_t ringA = lds_offset(s_ring), ringB = ringA + SA * A_STAGE;
@@ -187,8 +191,8 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   const int slot = wg >> 3;
   const int tile = ((slot / p.chunk) * 8 + (wg & 7)) * p.chunk + slot % p.chunk;
   if (tile >= p.total) return;
-  const int split = (MODE == 3) ? tile % p.S : 0;   // which share of the tile's reduction
-  const int tile_id = (MODE == 3) ? tile / p.S : tile;
+  const int split = SHARES ? tile % p.S : 0;   // which share of the tile (MODE 3: part of the reduction, MODE 4: head)
+  const int tile_id = SHARES ? tile / p.S : tile;
   const int qt = tile_id % p.nqt;
   const int pt = (tile_id / p.nqt) % p.npt;
   const int lz = tile_id / (p.nqt * p.npt);  // layer, or group of layers in mode 2
@@ -253,9 +257,11 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // one head's [T][Dh] slice.
   // MODE 3: one phase of (D/kBK)/(S/2) steps, starting at step u_first of the K tensor (shares
   // 0 .. S/2-1) or of the V tensor (the others).
-  const int sps = (MODE == 3) ? (D / kBK) / (p.S / 2) : (MODE != 1) ? (D / kBK) : (p.T * 2);
-  const int nphase = (MODE == 3) ? 1 : (MODE != 1) ? 2 : 2 * p.H;
-  const int tok = (MODE != 1) ? 256 : p.H * 256;
+  // MODE 4: the two phases of head `split`, i.e. phases 2*split and 2*split + 1 of MODE 1.
+  const int sps = (MODE == 3) ? (D / kBK) / (p.S / 2) : !PER_HEAD ? (D / kBK) : (p.T * 2);
+  const int nphase = (MODE == 3) ? 1 : (MODE == 4) ? 2 * split + 2 : !PER_HEAD ? 2 : 2 * p.H;
+  const int ph_first = (MODE == 4) ? 2 * split : 0;
+  const int tok = !PER_HEAD ? 256 : p.H * 256;
   const bool split_v = (MODE == 3) && split >= p.S / 2;
   const int u_first = (MODE == 3) ? (split % (p.S / 2)) * sps : 0;
   auto advance = [&](Cursor& c) {
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     i32x4 srd;
     uint32_t off, dst;
   };
-  Feed fa{{0, 0}, 0, srdAk, 0, 0}, fb{{0, 0}, 0, srdBk, 0, 0};
+  Feed fa{{0, ph_first}, 0, srdAk, 0, 0}, fb{{0, ph_first}, 0, srdBk, 0, 0};
   auto prepare = [&](Feed& f, const i32x4& k_srd, const i32x4& v_srd, uint32_t ring, int stage_bytes) {
     f.srd = ((MODE == 3) ? split_v : (f.cur.ph & 1) != 0) ? v_srd : k_srd;
     f.off = byte_off(f.cur);
@@ -366,7 +372,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 
   // ---- scale factors, read from the cached squared norms when a phase ends.  Range-checked
   // buffer loads with 32-bit offsets: a row past the end of the pool / queries reads 0.
-  const int nh = (MODE != 1) ? 1 : p.H;
+  const int nh = !PER_HEAD ? 1 : p.H;
   __amdgpu_buffer_rsrc_t nQk, nQv, nPk, nPv;
   auto set_layer_norms = [&]() {
     nQk = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q_ksq + (long long)l * p.Q * nh), 0, p.Q * nh * 4, 0x00020000);
@@ -390,7 +396,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // Pool rows row .. row+3 of the tile: ratio rp = aK/aV and final factor fp = aV.
   auto pool_scales = [&](int row, int head, f32x4& rp, f32x4& fp) {
     f32x4 ksq, vsq;
-    if (MODE != 1) {
+    if (!PER_HEAD) {
       typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
       ksq = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nPk, (p0 + row) * 4, 0, 0));
       vsq = __builtin_bit_cast(f32x4, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(nPv, (p0 + row) * 4, 0, 0));
@@ -574,6 +580,10 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     }
   } else if (MODE == 3) {
     run_phase();
+  } else if (MODE == 4) {
+    run_phase();
+    rescale(split);
+    run_phase();
   } else {
     for (int li = 0;;) {
       run_phase();
@@ -600,11 +610,12 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 
   if (MODE == 2) return;  // the sums of this group's layers are in place, tile by tile in register order
 
-  if (MODE == 3) {
-    // this share of the tile's scores, in register order like the sums of the layer-mean mode:
-    // shares are laid out [layer][share][pool tile][query tile]
+  if (SHARES) {
+    // this share of the tile's scores (MODE 4: the score of head `split`), in register order like
+    // the sums of the layer-mean mode: shares are laid out [layer][share][pool tile][query tile]
+    const int head = (MODE == 4) ? split : 0;
     float rq[TQ], fq[TQ];
-    query_scales(0, rq, fq);
+    query_scales(head, rq, fq);
     const long long tile_lin = (((long long)lz * p.S + split) * p.npt + pt) * p.nqt + qt;
     f32x4* out = reinterpret_cast<f32x4*>(p.dpart) + tile_lin * (BP * BQ / 4) + (long long)wave * (TP * 4 * TQ * 64) + lane;
 #pragma unroll
@@ -612,14 +623,14 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         f32x4 rp, fp;
-        pool_scales(row_of(i, g), 0, rp, fp);
+        pool_scales(row_of(i, g), head, rp, fp);
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
           f32x4 d;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            // fq fp = aVq aVp / 2; rq rp = (aKq aKp) / (aVq aVp)
-            const float f = split_v ? fq[j] * fp[e] : (rq[j] * fq[j]) * (rp[e] * fp[e]);
+            // fq fp = aVq aVp / 2; rq rp = (aKq aKp) / (aVq aVp); in MODE 4 the K part was rescaled at the phase end
+            const float f = (MODE == 4 || split_v) ? fq[j] * fp[e] : (rq[j] * fq[j]) * (rp[e] * fp[e]);
             d[e] = acc[i][j][4 * g + e] * f;
           }
           out[((i * 4 + g) * TQ + j) * 64] = d;
@@ -739,11 +750,13 @@ __device__ __forceinline__ int sum_index(int r, int c) {
 // groups.  Layer-mean mode: groups = groups of layers, scale = 1/(2dhN), so "higher wins, equal
 // goes to the lower index" on -distance picks the nearest live pool block.  Split mode: groups =
 // the shares of a tile's reduction, scale = -1, the value is the score; blockIdx.z is the layer.
+// take_min: the groups are combined by the minimum instead of the sum (per-head-all score, one
+// share per head).
 // grid = (query tiles of 64, pool chunks of sel_rows rows, layers); sel_rows is a multiple of 16;
 // a thread owns one query column and every fourth group of four rows.
 __global__ __launch_bounds__(256) void tile_sums_select_kernel(const float* __restrict__ dpart, int groups, int P,
                                                                int Q, int npt, int nqt, int sel_rows, float scale,
-                                                               const uint8_t* __restrict__ live,
+                                                               int take_min, const uint8_t* __restrict__ live,
                                                                Part* __restrict__ part) {
   __shared__ Part s_part[4][64];
   const int tq = threadIdx.x & 63, tp = threadIdx.x >> 6;
@@ -759,15 +772,24 @@ __global__ __launch_bounds__(256) void tile_sums_select_kernel(const float* __re
     for (int r = pbeg + 4 * tp; r < pend; r += 16) {
       const float* src = dpart + ((long long)(r >> 8) * nqt + (q >> 8)) * 65536 + sum_index(r & 255, q & 255);
       f32x4 sum = {0.f, 0.f, 0.f, 0.f};  // groups are added in ascending order: the same bits on every run
-      int g = 0;
-      for (; g + 4 <= groups; g += 4) {
-        f32x4 v[4];
+      if (take_min) {
+        sum = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src));
+        for (int g = 1; g < groups; ++g) {
+          const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + g * gstride));
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + (g + u) * gstride));
+          for (int e = 0; e < 4; ++e) sum[e] = fminf(sum[e], v[e]);
+        }
+      } else {
+        int g = 0;
+        for (; g + 4 <= groups; g += 4) {
+          f32x4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) sum += v[u];
+          for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + (g + u) * gstride));
+#pragma unroll
+          for (int u = 0; u < 4; ++u) sum += v[u];
+        }
+        for (; g < groups; ++g) sum += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + g * gstride));
       }
-      for (; g < groups; ++g) sum += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + g * gstride));
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (r + e < pend && (!live || live[r + e])) top2_push(-(sum[e] * scale), r + e, best, bidx, second);
@@ -901,16 +923,24 @@ inline size_t layer_mean_part_offset(int groups, int64_t npt, int64_t nqt) {
 // constants come from measurements of 1 to 144 tiles of the 256 x 256 shape (within 10 % from 64
 // tiles up; a single layer of 16 tiles takes 143 us against 112 estimated).  A share has at least
 // 8 steps; the shares of all tiles take at most 512 MB; problems of more than one round are left
-// alone.  With at most 128 query blocks the whole-tile
+// alone.  In per-head mode the shares are the H heads (the score is a minimum over heads, not a
+// sum over the reduction), chosen by the same estimate.  With at most 128 query blocks the whole-tile
 // path has its narrow tiles, so the split is only used below half a round there.  Block mode only.
 // The decision depends on the shape alone (an MI355X has 256 compute units), so that the workspace
 // size does not depend on the device that happens to be current.
 constexpr int kSplitComputeUnits = 256;
 inline int split_count(int mode, int64_t L, int64_t P, int64_t Q, int T, int H) {
-  if (mode != RC_SCORE_BLOCK || P <= 0 || Q <= 0 || L <= 0) return 1;
+  if (P <= 0 || Q <= 0 || L <= 0) return 1;
   const int64_t tiles = L * ((P + 255) / 256) * ((Q + 255) / 256);
   if (tiles > kSplitComputeUnits) return 1;  // more than one round: measured gains of 0-6 % only (workgroups of
                                              // later rounds start as earlier ones end, the rounds are not that rigid)
+  if (mode == RC_SCORE_PER_HEAD_ALL) {
+    if (H < 2 || tiles * H > 2048) return 1;
+    auto rounds = [&](int64_t wgs) { return (double)((wgs + kSplitComputeUnits - 1) / kSplitComputeUnits); };
+    const double whole = rounds(tiles) * (4.0 * T * H + 6.0);
+    const double heads = rounds(tiles * H) * (4.0 * T + 6.0) + 0.03 * (double)(tiles * H) + 5.0;
+    return heads < 0.9 * whole ? H : 1;
+  }
   if (Q <= 128 && tiles * 2 > kSplitComputeUnits) return 1;
   const int steps = T * H * 128 / kBK;  // per tensor
   auto estimate = [&](int S) {
@@ -1043,15 +1073,23 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.stagger_unit = 0;
     const int64_t per_round = 8LL * mp.chunk;
     const unsigned grid = (unsigned)(((mp.total + per_round - 1) / per_round) * per_round);
-    if (qdesc->dtype == RC_BF16)
-      match_tile_kernel<true, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
-    else
-      match_tile_kernel<false, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
+    const bool heads = mode == RC_SCORE_PER_HEAD_ALL;
+    if (qdesc->dtype == RC_BF16) {
+      if (heads)
+        match_tile_kernel<true, 256, 256, 4><<<grid, kThreads, 0, st>>>(mp);
+      else
+        match_tile_kernel<true, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
+    } else {
+      if (heads)
+        match_tile_kernel<false, 256, 256, 4><<<grid, kThreads, 0, st>>>(mp);
+      else
+        match_tile_kernel<false, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
+    }
     if (rc_status s = check_launch("rc_match_blocks(tile shares)")) return s;
     Part* part = reinterpret_cast<Part*>(static_cast<char*>(workspace) + sl.part_offset);
     const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)sl.nchunks, (unsigned)L);
     tile_sums_select_kernel<<<sgrid, 256, 0, st>>>(mp.dpart, S, (int)P, (int)Q, (int)sl.npt, (int)sl.nqt, sl.sel_rows,
-                                                   -1.0f, pool_live, part);
+                                                   -1.0f, heads ? 1 : 0, pool_live, part);
     if (rc_status s = check_launch("rc_match_blocks(select)")) return s;
     match_finalize_kernel<<<(unsigned)((LQ + 255) / 256), 256, 0, st>>>(part, (int)sl.nchunks, LQ, (int)Q, tau, best_idx,
                                                                        best_score, match_idx, second_score);
@@ -1186,7 +1224,7 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     if (rc_status s = check_launch("rc_match_blocks_layer_mean(tiles)")) return s;
     const float scale = 1.0f / ((float)L * 2.0f * (float)qdesc->block_tokens * (float)qdesc->n_kv_heads);
     const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)nchunks);
-    tile_sums_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, (int)npt, (int)nqt, sel_rows, scale,
+    tile_sums_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, (int)npt, (int)nqt, sel_rows, scale, 0,
                                                     pool_live, part);
     if (rc_status s = check_launch("rc_match_blocks_layer_mean(select)")) return s;
   }

@@ -69,11 +69,13 @@ def test_match_validation(lib):
                          kw.get("kq", FAKE), FAKE, kw.get("Q", 4), FAKE, FAKE, FAKE, FAKE, kw.get("P", 64), FAKE, FAKE,
                          None, kw.get("tau", 0.9), FAKE, FAKE, FAKE, None, kw.get("ws", FAKE), kw.get("wsb", 1 << 26),
                          None]
-    # per-head mode, and block mode with more than 128 tiles: one 16-byte partial per (layer, pool tile, query)
-    assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 64) == 2 * 1 * 4 * 16
-    assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 257) == 2 * 2 * 4 * 16
+    # more than one round of tiles: one 16-byte partial per (layer, pool tile, query)
     many = desc(L=200, n=4)
     assert lib.rc_match_workspace_size(ctypes.byref(many), 0, 4, 257) == 200 * 2 * 4 * 16
+    assert lib.rc_match_workspace_size(ctypes.byref(many), 1, 4, 257) == 200 * 2 * 4 * 16
+    # per-head mode with few tiles: one share of 256 KB per head and tile, then the partials of the pool chunks
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 64) == 2 * 8 * 65536 * 4 + 2 * 2 * 4 * 16
+    assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 257) == 2 * 8 * 2 * 65536 * 4 + 2 * 9 * 4 * 16
     # block mode with few tiles: 2 tiles x 64 shares of 256 KB, then 2 pool chunks of partials per layer
     assert lib.rc_match_workspace_size(ctypes.byref(q), 0, 4, 64) == 2 * 64 * 65536 * 4 + 2 * 2 * 4 * 16
     assert lib.rc_match_workspace_size(ctypes.byref(q), 9, 4, 64) == 0

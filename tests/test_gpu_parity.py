@@ -211,6 +211,17 @@ def test_per_head_mode(oracle, dtype):
     assert (gpu["match_idx"][1][slots] >= 0).all()
 
 
+def test_per_head_many_layers_whole_tiles(oracle):
+    # more than one round of tiles: one workgroup per tile walks all heads and keeps the running minimum in
+    # 16-bit fixed point (the small per-head cases take the one-share-per-head path instead)
+    w = synth.scaled(synth.WORKLOADS[5], name="perhead_whole_tiles", L=90, P=513, Q=40, T=16, R=2, E=300, seed=15)
+    say(w.name)
+    pr = synth.make_problem(w, DEV)
+    live = pr["live"].clone()
+    live[:, 7] = 0
+    full_check(oracle, w, pr, live)
+
+
 def test_per_head_T16_H4(oracle):
     w = synth.scaled(synth.WORKLOADS[5], name="perhead_T16_H4", L=1, P=130, Q=33, T=16, H=4, R=1, E=163, seed=14)
     say(w.name)
