@@ -20,7 +20,7 @@ PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # dense MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of match_tile_kernel from rocprofv3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scales
 # that the 1 GiB copy at the start of this script gives); see profiles/bench_cfg2_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"cfg2_qwq32b_step": 18.49e9}
+MEASURED_TRAFFIC_BYTES = {"cfg2_qwq32b_step": 18.56e9}
 
 
 def log(msg):
