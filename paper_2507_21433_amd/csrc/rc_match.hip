@@ -207,8 +207,8 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // in time by the position of their pool tile within the XCD's run of tiles (the query tiles of
   // one pool tile stay together: the second one finds the pool slice in the L2 only if it follows
   // closely); later rounds inherit the spread.  Nothing else changes.  Measured on one box against
-  // an unspread start: 3-5 % faster with one query tile (Q = 256), 3.5 % and 5-10 % with four
-  // (Q = 1024, pools of 16 K and 48 K blocks), no difference in per-head mode.
+  // an unspread start: 3 % faster with one query tile (Q = 256), 5 % in per-head mode (Q = 512),
+  // within 0.5 % with four query tiles (Q = 1024).
   if (wg < p.stagger_wgs)
     for (int i = 0; i < (((slot % p.chunk) / p.nqt) & 15) * p.stagger_unit; ++i) __builtin_amdgcn_s_sleep(16);
 
