@@ -45,9 +45,25 @@ def cpu_baseline(w, pr, max_layers):
     rc_oracle.match(0 if w.dtype == "f16" else 1, w.mode, *a, live, w.tau)
     dt = time.time() - t0
     pairs = n_layers * w.P * n_q
-    return {"value": pairs / dt, "unit": "pairs/s", "cores": rc_oracle.n_threads(), "kind": "oracle",
-            "sample": f"rc_oracle.match on the first {n_q} of {w.Q} query blocks of the first {n_layers} of {w.L} layers "
-                      f"of {w.name} ({pairs} pairs, {dt:.1f} s)"}
+    res = {"value": pairs / dt, "unit": "pairs/s", "cores": rc_oracle.n_threads(), "kind": "oracle",
+           "sample": f"rc_oracle.match on the first {n_q} of {w.Q} query blocks of the first {n_layers} of {w.L} layers "
+                     f"of {w.name} ({pairs} pairs, {dt:.1f} s)"}
+    # the same oracle on one core, on a sixteenth of the sample (the first layer, fewer queries)
+    try:
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        n1 = int(max(1, min(n_q, pairs // 16 // w.P)))
+        a1 = [x[:1, :n1] if i < 2 else x[:1] for i, x in enumerate(a)]
+        gomp.omp_set_num_threads(1)
+        t0 = time.time()
+        rc_oracle.match(0 if w.dtype == "f16" else 1, w.mode, *a1, live[:1], w.tau)
+        dt1 = time.time() - t0
+        gomp.omp_set_num_threads(rc_oracle.n_threads())
+        res["one_core_value"] = w.P * n1 / dt1
+        res["one_core_sample"] = f"first {n1} query blocks of the first layer ({w.P * n1} pairs, {dt1:.1f} s)"
+    except OSError:
+        pass
+    return res
 
 
 def main():
