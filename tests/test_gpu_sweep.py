@@ -33,12 +33,36 @@ def draw(case):
                 planted_frac=float(r.choice([0.0, 0.3, 1.0])), seed=500 + case)
 
 
+def draw_many_layers(case):
+    """More than 256 tiles (one or two small tiles in each of 257-330 layers): the whole-tile paths, which the
+    few-layer shapes above never take."""
+    r = np.random.RandomState(3000 + case)
+    edges = [1, 2, 31, 33, 64, 65, 127, 129, 255, 257, 300]
+    T = int(r.choice([16, 32]))
+    H = int(r.choice([1, 2, 3, 5, 8]))
+    L = int(r.randint(257, 331))
+    budget = 2e10 / (T * H * 128) / L
+    small = 2e9 / (T * H * 128 * 4) / L               # pool blocks that keep the KV of the case under 2 GB
+    P = int(r.choice([e for e in edges if e <= min(budget, small)] or [1]))
+    Q = int(r.choice([e for e in edges if e * P <= budget] or [1]))
+    return dict(L=L, P=P, Q=Q, T=T, H=H, mode=int(r.randint(0, 2)), dtype=str(r.choice(["f16", "bf16"])),
+                planted_frac=float(r.choice([0.0, 0.3, 1.0])), seed=900 + case)
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_random_shape_many_layers(oracle, case):
+    run_shape(oracle, draw_many_layers(case), f"layers{case}", case)
+
+
 @pytest.mark.parametrize("case", range(24))
 def test_random_shape(oracle, case):
-    kw = draw(case)
+    run_shape(oracle, draw(case), f"sweep{case}", case)
+
+
+def run_shape(oracle, kw, name, case):
     planted = min(int(kw["planted_frac"] * kw["Q"]), kw["P"])
     kw["planted_frac"] = planted / kw["Q"]
-    w = synth.scaled(synth.WORKLOADS[2], name=f"sweep{case}", R=1, E=kw["P"] + kw["Q"], **kw)
+    w = synth.scaled(synth.WORKLOADS[2], name=name, R=1, E=kw["P"] + kw["Q"], **kw)
     say(f"{w.name}: L={w.L} P={w.P} Q={w.Q} T={w.T} H={w.H} mode={w.mode} {w.dtype} planted={planted}")
     pr = synth.make_problem(w, DEV)
     d = 0 if w.dtype == "f16" else 1
