@@ -23,7 +23,7 @@ def run_mutant(workdir, name):
 
 
 @pytest.fixture(scope="module")
-def verdicts(tmp_path_factory):
+def outcomes(tmp_path_factory):
     """Every mutant built and judged once, a few at a time (each run is a child process of a few seconds)."""
     from concurrent.futures import ThreadPoolExecutor
     workdir = str(tmp_path_factory.mktemp("mutants"))
@@ -38,7 +38,7 @@ def test_mutant_names_are_unique():
 
 
 @pytest.mark.parametrize("name", [m[0] for m in MUTANTS])
-def test_pins_reject_mutant(verdicts, name):
-    code, tail = verdicts[name]
+def test_pins_reject_mutant(outcomes, name):
+    code, tail = outcomes[name]
     # 1 = some pin failed (what must happen); 0 = the mistake went unnoticed; anything else = the suite itself broke
     assert code == 1, f"mutant {name}: pin suite exit code {code}\n{tail}"
