@@ -266,12 +266,13 @@ size_t rc_pat_workspace_size(void);
  * are left out; with no finite sample the threshold is -inf, which shares nothing.
  *
  *   samples         DEVICE float [n], n < 2^31, any order
- *   p               percentile in [0, 100]
+ *   p               percentile in [0, 100], a double: the rank is formed from exactly the value the caller
+ *                   passes (p = 0.1 with n_f = 1000 is rank 1; rounded to float it would be rank 2)
  *   threshold       DEVICE float [1], written on the stream (no host synchronisation)
  *   n_finite        DEVICE int64 [1] or NULL: number of samples that took part
  *   workspace       DEVICE, >= rc_pat_workspace_size() bytes, 16-byte aligned, scratch
  */
-rc_status rc_pat_threshold(const float* samples, int64_t n, float p,
+rc_status rc_pat_threshold(const float* samples, int64_t n, double p,
                            float* threshold, int64_t* n_finite,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 

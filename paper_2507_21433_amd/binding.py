@@ -68,7 +68,7 @@ def lib():
         L.rc_match_blocks_layer_mean.restype = i32
         L.rc_pat_workspace_size.argtypes = []
         L.rc_pat_workspace_size.restype = sz
-        L.rc_pat_threshold.argtypes = [vp, i64, f32, vp, vp, vp, sz, vp]
+        L.rc_pat_threshold.argtypes = [vp, i64, ctypes.c_double, vp, vp, vp, sz, vp]
         L.rc_pat_threshold.restype = i32
         L.rc_apply_threshold.argtypes = [vp, vp, i64, vp, vp, vp]
         L.rc_apply_threshold.restype = i32

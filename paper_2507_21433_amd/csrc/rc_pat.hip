@@ -146,12 +146,12 @@ __global__ __launch_bounds__(256) void apply_threshold_kernel(const int32_t* __r
 
 extern "C" size_t rc_pat_workspace_size(void) { return sizeof(rc::PatState); }
 
-extern "C" rc_status rc_pat_threshold(const float* samples, int64_t n, float p, float* threshold, int64_t* n_finite,
+extern "C" rc_status rc_pat_threshold(const float* samples, int64_t n, double p, float* threshold, int64_t* n_finite,
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
   using namespace rc;
   clear_error();
   if (n < 0 || n > 0x7fffffffLL) return fail(RC_ERR_INVALID_ARG, "rc_pat_threshold: n = %lld outside [0, 2^31)", (long long)n);
-  if (!(p >= 0.f && p <= 100.f)) return fail(RC_ERR_INVALID_ARG, "rc_pat_threshold: p = %g outside [0, 100]", (double)p);
+  if (!(p >= 0.0 && p <= 100.0)) return fail(RC_ERR_INVALID_ARG, "rc_pat_threshold: p = %g outside [0, 100]", p);
   if (!threshold || (n > 0 && !samples)) return fail(RC_ERR_INVALID_ARG, "rc_pat_threshold: NULL samples or threshold");
   if (!workspace || workspace_bytes < sizeof(PatState) || !aligned16(workspace))
     return fail(RC_ERR_WORKSPACE, "rc_pat_threshold: workspace of %zu bytes needed (16-byte aligned), got %zu",
@@ -164,11 +164,11 @@ extern "C" rc_status rc_pat_threshold(const float* samples, int64_t n, float p, 
     long long wgs = (n + kPatThreads * 16 - 1) / (kPatThreads * 16);  // about 16 samples per thread
     if (wgs > 2048) wgs = 2048;
     for (int pass = 0; pass < 4; ++pass) {
-      pat_hist_kernel<<<(unsigned)wgs, kPatThreads, 0, st>>>(samples, (long long)n, (double)p, state, pass);
+      pat_hist_kernel<<<(unsigned)wgs, kPatThreads, 0, st>>>(samples, (long long)n, p, state, pass);
       if (rc_status s = check_launch("rc_pat_threshold(histogram)")) return s;
     }
   }
-  pat_final_kernel<<<1, kPatThreads, 0, st>>>((long long)n, (double)p, state, threshold,
+  pat_final_kernel<<<1, kPatThreads, 0, st>>>((long long)n, p, state, threshold,
                                               reinterpret_cast<long long*>(n_finite));
   return check_launch("rc_pat_threshold(final)");
 }

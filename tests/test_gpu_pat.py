@@ -36,9 +36,9 @@ def test_pat_random(oracle, n):
     s = np.where(rng.rand(n) < 0.3, 0.15 + 0.01 * rng.randn(n), 1.41 + 0.005 * rng.randn(n)).astype(np.float32)
     s[rng.rand(n) < 0.05] = np.float32(0.15)
     s[rng.rand(n) < 0.02] = np.inf
-    for p in (0.0, 20.0, 50.0, 80.0, 99.5, 100.0):
+    for p in (0.0, 0.1, 20.0, 33.3, 50.0, 80.0, 99.5, 100.0):
         t, c = gpu_pat(s, p)
-        to, co = oracle.pat_threshold(s, float(np.float32(p)))
+        to, co = oracle.pat_threshold(s, p)
         assert c == co and same(t, to), (n, p, t, to)
 
 
@@ -55,13 +55,23 @@ def test_pat_special_values(oracle):
     for s in cases:
         for p in (0.0, 10.0, 33.3, 50.0, 80.0, 100.0):
             t, c = gpu_pat(s, p)
-            to, co = oracle.pat_threshold(s, float(np.float32(p)))
+            to, co = oracle.pat_threshold(s, p)
             assert c == co and (same(t, to) or (t == 0 and to == 0)), (s[:4], p, t, to)
     t, c = gpu_pat(np.zeros(0, dtype=np.float32), 80.0)
     assert np.isneginf(t) and c == 0
     with pytest.raises(rc.RcError) as e:
         rc.rc_pat_threshold(torch.zeros(4, device=DEV), 101.0)
     assert e.value.code == 1
+
+
+def test_pat_rank_comes_from_the_callers_double(oracle):
+    """p = 0.1 of 1000 samples is rank ceil(1.0) = 1; the same p rounded to float (0.100000001...) would give rank 2."""
+    say("pat: p = 0.1, n = 1000 (rank 1 in double, 2 if p were rounded to float)")
+    s = np.random.RandomState(8).permutation(1000).astype(np.float32) + 5
+    t, c = gpu_pat(s, 0.1)
+    to, co = oracle.pat_threshold(s, 0.1)
+    assert c == co == 1000 and t == to == 5.0
+    assert oracle.pat_threshold(s, float(np.float32(0.1)))[0] == 6.0      # what the float ABI used to compute
 
 
 def test_apply_threshold(oracle):

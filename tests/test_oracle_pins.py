@@ -529,6 +529,11 @@ def test_pat_hand_cases(oracle):
     assert oracle.pat_threshold(np.array([2, 2, 2, 7], dtype=np.float32), 75)[0] == 2
     assert oracle.pat_threshold(np.array([2, 2, 2, 7], dtype=np.float32), 76)[0] == 7
     assert oracle.pat_threshold(np.array([9], dtype=np.float32), 0)[0] == 9
+    # the rank is formed from the double the caller passes: 0.1 % of 1000 samples is exactly one sample (the smallest);
+    # the same percentile rounded to float first (0.100000001...) would reach the second
+    s1000 = np.arange(1000, dtype=np.float32)[::-1].copy()
+    assert oracle.pat_threshold(s1000, 0.1)[0] == 0
+    assert oracle.pat_threshold(s1000, 0.2)[0] == 1
 
 
 def test_pat_vs_library_quantile_and_definition(oracle):
