@@ -163,6 +163,30 @@ rc_status rc_remap_block_table(int32_t n_layers,
                                uint8_t* freed, int32_t* n_remapped,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Bytes of the library's built-in scratch buffer behind rc_remap_block_table_static. */
+#define RC_REMAP_STATIC_SCRATCH_BYTES (4u << 20)
+size_t rc_remap_static_scratch_size(void);
+
+/*
+ * rc_remap_block_table for callers that cannot allocate or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results; the scratch memory is a buffer of
+ * RC_REMAP_STATIC_SCRATCH_BYTES (4 MiB) that is part of the library's device code, one copy per
+ * GPU, held until the process ends.  The call allocates and frees nothing and does not synchronise.
+ * A problem whose rc_remap_workspace_size() exceeds the buffer is refused with RC_ERR_WORKSPACE
+ * before anything is launched (the five benchmark workloads need at most 3.3 MB).  Every call on
+ * one GPU uses that GPU's buffer: calls on the same GPU must not overlap in time (on different
+ * streams, or from different threads), or they race on it.  No part of the buffer has to be
+ * cleared between calls: the kernels validate or overwrite everything they read from it.
+ */
+rc_status rc_remap_block_table_static(int32_t n_layers,
+                                      const int32_t* tables_in, int32_t* tables_out,
+                                      int64_t R, int64_t E,
+                                      const int32_t* query_ids, const int32_t* pool_ids,
+                                      const int32_t* match_idx, int64_t Q, int64_t P, int64_t NB,
+                                      const int32_t* refcount_in, int32_t* refcount_out,
+                                      uint8_t* freed, int32_t* n_remapped, void* hip_stream);
+
 /*
  * Candidate-restricted scoring: Stage 2 in the shape the paper runs it (Sec. IV-A:
  * only the blocks of the steps that Stage 1 flagged are compared; k candidates per

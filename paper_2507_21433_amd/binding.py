@@ -17,7 +17,7 @@ RC_F16, RC_BF16 = 0, 1
 RC_SCORE_BLOCK, RC_SCORE_PER_HEAD_ALL = 0, 1
 
 EXPORTS = ("rc_block_norms", "rc_match_workspace_size", "rc_match_blocks", "rc_remap_workspace_size",
-           "rc_remap_block_table", "rc_score_candidates", "rc_layer_mean_workspace_size", "rc_match_blocks_layer_mean",
+           "rc_remap_block_table", "rc_remap_static_scratch_size", "rc_remap_block_table_static", "rc_score_candidates", "rc_layer_mean_workspace_size", "rc_match_blocks_layer_mean",
            "rc_pat_workspace_size", "rc_pat_threshold", "rc_apply_threshold", "rc_pool_admit_workspace_size", "rc_pool_admit",
            "rc_candidate_distances_workspace_size", "rc_candidate_distances", "rc_last_error", "rc_version")
 
@@ -58,6 +58,10 @@ def lib():
         L.rc_remap_block_table.argtypes = [i32, vp, vp, i64, i64, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp,
                                            vp, sz, vp]
         L.rc_remap_block_table.restype = i32
+        L.rc_remap_static_scratch_size.argtypes = []
+        L.rc_remap_static_scratch_size.restype = sz
+        L.rc_remap_block_table_static.argtypes = [i32, vp, vp, i64, i64, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp]
+        L.rc_remap_block_table_static.restype = i32
         L.rc_score_candidates.argtypes = [dp, dp, i32, vp, vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, vp, i64, f32,
                                           vp, vp, vp, vp, vp]
         L.rc_score_candidates.restype = i32
@@ -198,6 +202,25 @@ def rc_remap_block_table(tables, query_ids, pool_ids, match_idx, P, NB, refcount
                                       _ptr(match_idx), Q, P, NB, _ptr(refcount), _ptr(r_out), _ptr(freed),
                                       _ptr(n_remapped), _ptr(workspace), workspace.numel(), _stream()))
     return dict(tables=t_out, refcount=r_out, freed=freed, n_remapped=n_remapped)
+
+
+def rc_remap_block_table_static(tables, query_ids, pool_ids, match_idx, P, NB, refcount, out):
+    """rc_remap_block_table on the library's built-in scratch buffer: no workspace, and every output is the caller's (`out`)."""
+    _dev(tables, query_ids, pool_ids, match_idx, refcount, out["tables"], out["refcount"], out["freed"], out["n_remapped"])
+    assert tables.dtype == torch.int32 and tables.dim() == 3 and tables.is_contiguous()
+    L, R, E = tables.shape
+    Q = query_ids.numel()
+    assert query_ids.dtype == torch.int32 and match_idx.dtype == torch.int32 and match_idx.shape == (L, Q)
+    assert match_idx.is_contiguous() and refcount.dtype == torch.int32 and refcount.shape == (L, NB)
+    assert refcount.is_contiguous()
+    if pool_ids is not None:
+        assert pool_ids.dtype == torch.int32 and pool_ids.numel() == P
+    assert out["tables"].shape == tables.shape and out["refcount"].shape == refcount.shape
+    assert out["freed"].shape == (L, Q) and out["freed"].dtype == torch.uint8 and out["n_remapped"].shape == (L,)
+    _check(lib().rc_remap_block_table_static(L, _ptr(tables), _ptr(out["tables"]), R, E, _ptr(query_ids), _ptr(pool_ids),
+                                             _ptr(match_idx), Q, P, NB, _ptr(refcount), _ptr(out["refcount"]),
+                                             _ptr(out["freed"]), _ptr(out["n_remapped"]), _stream()))
+    return out
 
 
 def rc_score_candidates(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, pool_live, cand, tau, mode=RC_SCORE_BLOCK, out=None):

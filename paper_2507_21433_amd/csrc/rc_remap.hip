@@ -15,6 +15,8 @@
 //                small claim table in LDS, one winner per slot and round.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "rc_common.hpp"
 
 namespace rc {
@@ -267,28 +269,34 @@ extern "C" size_t rc_remap_workspace_size(int32_t n_layers, int64_t R, int64_t E
   return (size_t)(ints > 0 ? ints : 4) * sizeof(int32_t);
 }
 
-extern "C" rc_status rc_remap_block_table(int32_t n_layers, const int32_t* tables_in, int32_t* tables_out, int64_t R,
-                                          int64_t E, const int32_t* query_ids, const int32_t* pool_ids,
-                                          const int32_t* match_idx, int64_t Q, int64_t P, int64_t NB,
-                                          const int32_t* refcount_in, int32_t* refcount_out, uint8_t* freed,
-                                          int32_t* n_remapped, void* workspace, size_t workspace_bytes,
-                                          void* hip_stream) {
-  using namespace rc;
-  clear_error();
+// Scratch of rc_remap_block_table_static: one array per GPU, part of the loaded code object, so it
+// exists from the moment the library is loaded on a device until the process ends.  In host code
+// the name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[RC_REMAP_STATIC_SCRATCH_BYTES];
+
+namespace rc {
+namespace {
+
+// Validation and the three launches, shared by the two entry points; `who` names the caller in
+// error texts.  Nothing is allocated here.
+rc_status remap_run(const char* who, int32_t n_layers, const int32_t* tables_in, int32_t* tables_out, int64_t R,
+                    int64_t E, const int32_t* query_ids, const int32_t* pool_ids, const int32_t* match_idx, int64_t Q,
+                    int64_t P, int64_t NB, const int32_t* refcount_in, int32_t* refcount_out, uint8_t* freed,
+                    int32_t* n_remapped, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (n_layers < 0 || R < 0 || E < 0 || Q < 0 || P < 0 || NB < 0)
-    return fail(RC_ERR_INVALID_ARG, "rc_remap_block_table: negative size");
-  if (Q > kMaxQ) return fail(RC_ERR_UNSUPPORTED, "rc_remap_block_table: Q %lld above %d", (long long)Q, kMaxQ);
-  if (!pool_ids && P > NB) return fail(RC_ERR_INVALID_ARG, "rc_remap_block_table: identity pool ids need P <= NB");
+    return fail(RC_ERR_INVALID_ARG, "%s: negative size", who);
+  if (Q > kMaxQ) return fail(RC_ERR_UNSUPPORTED, "%s: Q %lld above %d", who, (long long)Q, kMaxQ);
+  if (!pool_ids && P > NB) return fail(RC_ERR_INVALID_ARG, "%s: identity pool ids need P <= NB", who);
   if (n_layers == 0) return RC_OK;
   const int64_t RE = R * E;
   if (n_layers > 65535 || NB > 0x7fffffffLL || P > 0x7fffffffLL || RE > (1LL << 40))
-    return fail(RC_ERR_UNSUPPORTED, "rc_remap_block_table: problem beyond the grid limits");
+    return fail(RC_ERR_UNSUPPORTED, "%s: problem beyond the grid limits", who);
   if (!n_remapped || (RE > 0 && (!tables_in || !tables_out)) || (NB > 0 && (!refcount_in || !refcount_out)) ||
       (Q > 0 && (!query_ids || !match_idx || !freed)))
-    return fail(RC_ERR_INVALID_ARG, "rc_remap_block_table: NULL pointer");
+    return fail(RC_ERR_INVALID_ARG, "%s: NULL pointer", who);
   const size_t need = rc_remap_workspace_size(n_layers, R, E, Q, NB);
   if (!workspace || workspace_bytes < need || !aligned16(workspace))
-    return fail(RC_ERR_WORKSPACE, "rc_remap_block_table: workspace of %zu bytes needed (16-byte aligned), got %zu",
+    return fail(RC_ERR_WORKSPACE, "%s: workspace of %zu bytes needed (16-byte aligned), got %zu", who,
                 need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   int32_t* slot_of = static_cast<int32_t*>(workspace);
@@ -320,4 +328,69 @@ extern "C" rc_status rc_remap_block_table(int32_t n_layers, const int32_t* table
                                                                       (int)Q, (int)P, NB, refcount_out, freed,
                                                                       n_remapped);
   return check_launch("rc_remap_block_table(finalize)");
+}
+
+constexpr size_t kStaticScratchBytes = RC_REMAP_STATIC_SCRATCH_BYTES;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, nullptr = not asked yet
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+rc_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(RC_ERR_DEVICE, "rc_remap_block_table_static: hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices)
+    return fail(RC_ERR_UNSUPPORTED, "rc_remap_block_table_static: device %d beyond the %d devices kept track of", dev,
+                kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(RC_ERR_DEVICE, "rc_remap_block_table_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return RC_OK;
+}
+
+}  // namespace
+}  // namespace rc
+
+extern "C" rc_status rc_remap_block_table(int32_t n_layers, const int32_t* tables_in, int32_t* tables_out, int64_t R,
+                                          int64_t E, const int32_t* query_ids, const int32_t* pool_ids,
+                                          const int32_t* match_idx, int64_t Q, int64_t P, int64_t NB,
+                                          const int32_t* refcount_in, int32_t* refcount_out, uint8_t* freed,
+                                          int32_t* n_remapped, void* workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
+  rc::clear_error();
+  return rc::remap_run("rc_remap_block_table", n_layers, tables_in, tables_out, R, E, query_ids, pool_ids, match_idx, Q, P,
+                       NB, refcount_in, refcount_out, freed, n_remapped, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t rc_remap_static_scratch_size(void) { return rc::kStaticScratchBytes; }
+
+extern "C" rc_status rc_remap_block_table_static(int32_t n_layers, const int32_t* tables_in, int32_t* tables_out,
+                                                 int64_t R, int64_t E, const int32_t* query_ids,
+                                                 const int32_t* pool_ids, const int32_t* match_idx, int64_t Q,
+                                                 int64_t P, int64_t NB, const int32_t* refcount_in,
+                                                 int32_t* refcount_out, uint8_t* freed, int32_t* n_remapped,
+                                                 void* hip_stream) {
+  using namespace rc;
+  clear_error();
+  if (n_layers < 0 || R < 0 || E < 0 || Q < 0 || P < 0 || NB < 0)
+    return fail(RC_ERR_INVALID_ARG, "rc_remap_block_table_static: negative size");
+  const size_t need = rc_remap_workspace_size(n_layers, R, E, Q, NB);
+  if (need > kStaticScratchBytes)
+    return fail(RC_ERR_WORKSPACE,
+                "rc_remap_block_table_static: this problem needs %zu bytes of scratch, the built-in buffer has %zu; "
+                "use rc_remap_block_table with a workspace of the caller's",
+                need, kStaticScratchBytes);
+  if (n_layers == 0) return RC_OK;
+  void* ptr = nullptr;
+  if (rc_status s = static_scratch(&ptr)) return s;
+  return remap_run("rc_remap_block_table_static", n_layers, tables_in, tables_out, R, E, query_ids, pool_ids, match_idx, Q,
+                   P, NB, refcount_in, refcount_out, freed, n_remapped, ptr, kStaticScratchBytes, hip_stream);
 }
