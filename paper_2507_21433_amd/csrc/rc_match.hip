@@ -64,6 +64,7 @@ struct MatchParams {
   int T, H;
   int npt, nqt;
   int total;  // L * npt * nqt (layer-mean mode: groups * npt * nqt)
+  int vgrid;  // virtual workgroups: total rounded up to whole rounds of 8 XCDs x chunk; the launch walks them
   int chunk;  // tiles handed to one XCD in a row
   int G;      // layer-mean mode: layers per group (one workgroup walks the layers of its group)
   int S;      // split mode: workgroups per tile, each over its own part of the reduction (even)
@@ -185,12 +186,17 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   __shared__ __attribute__((aligned(1024))) char s_ring[RING];
   const uint32_t ringA = lds_offset(s_ring), ringB = ringA + SA * A_STAGE;
 
-  // ---- which tile: consecutive runs of `chunk` tiles go to one XCD (workgroups are dealt
-  // round-robin to the 8 XCDs), so tiles that share operands share an L2.
-  const int wg = blockIdx.x;
+  // ---- which tiles: the launch has one workgroup per compute unit, and workgroup b walks the
+  // virtual workgroups b, b + gridDim.x, ... of a grid of p.vgrid (a fixed schedule; measured
+  // against one workgroup per tile it is neither faster nor slower).  Consecutive runs of `chunk`
+  // tiles go to one XCD (workgroups are dealt round-robin to the 8 XCDs and gridDim.x is a multiple
+  // of 8, so a workgroup stays on its XCD's tiles), so tiles that share operands share an L2.
+  for (int wg = blockIdx.x; wg < p.vgrid; wg += gridDim.x) {
+  // every wave is done with the ring (last fragments, epilogue scratch) before the next tile's loads land in it
+  if (wg != (int)blockIdx.x) __syncthreads();
   const int slot = wg >> 3;
   const int tile = ((slot / p.chunk) * 8 + (wg & 7)) * p.chunk + slot % p.chunk;
-  if (tile >= p.total) return;
+  if (tile >= p.total) continue;
   const int split = SHARES ? tile % p.S : 0;   // which share of the tile (MODE 3: part of the reduction, MODE 4: head)
   const int tile_id = SHARES ? tile / p.S : tile;
   const int qt = tile_id % p.nqt;
@@ -209,7 +215,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // closely); later rounds inherit the spread.  Nothing else changes.  Measured on one box against
   // an unspread start: 3 % faster with one query tile (Q = 256), 5 % in per-head mode (Q = 512),
   // within 0.5 % with four query tiles (Q = 1024).
-  if (wg < p.stagger_wgs)
+  if (wg == (int)blockIdx.x && wg < p.stagger_wgs)
     for (int i = 0; i < (((slot % p.chunk) / p.nqt) & 15) * p.stagger_unit; ++i) __builtin_amdgcn_s_sleep(16);
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -285,16 +291,32 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     uint32_t off, dst;
   };
   Feed fa{{0, ph_first}, 0, srdAk, 0, 0}, fb{{0, ph_first}, 0, srdBk, 0, 0};
-  auto prepare = [&](Feed& f, const i32x4& k_srd, const i32x4& v_srd, uint32_t ring, int stage_bytes) {
+  auto prepare_src = [&](Feed& f, const i32x4& k_srd, const i32x4& v_srd) {
     f.srd = ((MODE == 3) ? split_v : (f.cur.ph & 1) != 0) ? v_srd : k_srd;
     f.off = byte_off(f.cur);
-    f.dst = ring + f.stage * stage_bytes + wave * 1024;
   };
-  auto next = [&](Feed& f, int stages) {
+  auto prepare_dst = [&](Feed& f, uint32_t ring, int stage_bytes) { f.dst = ring + f.stage * stage_bytes + wave * 1024; };
+  auto prepare = [&](Feed& f, const i32x4& k_srd, const i32x4& v_srd, uint32_t ring, int stage_bytes) {
+    prepare_src(f, k_srd, v_srd);
+    prepare_dst(f, ring, stage_bytes);
+  };
+  // the next slice of the same phase: the cursor counts on and the offset follows (same tensor)
+  auto bump = [&](Feed& f) {
+    if (PER_HEAD)
+      f.off += (f.cur.u & 1) ? (uint32_t)(tok - 128) : 128u;
+    else
+      f.off += 128u;
+    ++f.cur.u;
+  };
+  auto move_cursor = [&](Feed& f) {
     Cursor n = f.cur;
     advance(n);
     if (n.ph < nphase) f.cur = n;
-    f.stage = (f.stage + 1 == stages) ? 0 : f.stage + 1;
+  };
+  auto next_stage = [&](Feed& f, int stages) { f.stage = (f.stage + 1 == stages) ? 0 : f.stage + 1; };
+  auto next = [&](Feed& f, int stages) {
+    move_cursor(f);
+    next_stage(f, stages);
   };
   auto dmaA = [&](int i) { dma16<true>(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16); };
   auto dmaB = [&](int i) { dma16<false>(fb.srd, voff, fb.off + i * load_stride, fb.dst + i * NT * 16); };
@@ -324,11 +346,54 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // step instead of arriving in bursts right after the barrier, when all four waves would ask
   // the LDS for 8 KB each at the same moment.  Measured on one box against a burst of eight
   // reads per sub-step: 5-7 % on the Q = 1024 workloads, 3-4 % in per-head mode, 1-2 % on cfg2.
+  // The scalar bookkeeping of the two feeds (which slice comes next, from which tensor, into which
+  // ring stage) and of the read stages rides in those rows too (`slot_work`), a few instructions per
+  // row, in the gap behind the instruction after the load's.  A wave issues one instruction every
+  // four cycles and a matrix instruction covers seven more issues; left at the end of the step the
+  // bookkeeping sits between the last matrix instruction of one step and the first of the next,
+  // some thirty scalar instructions with nothing to hide behind (measured: 200 of the 2400 cycles
+  // of a step).  Slot s is row s % TP of batch s / TP; the query loads are slots 0 .. LB-1, the
+  // pool loads slots LB .. LB+LA-1.  The pool feed moves on just before its loads, the query feed
+  // after its loads (for the next step), then the read stages of the next step.
+  // FAST steps are those whose two feeds stay inside the phase (all but the last two of a phase):
+  // the cursor just counts and the tensor does not change; the last two steps take the general code.
   static_assert(TQ <= TP, "B fragment j is read behind row tile j");
-  auto batch = [&](const uint4 (&af)[TP], const uint4 (&bf)[TQ], int b, const char* sA, const char* sB, int kk,
-                   uint4 (&naf)[TP], uint4 (&nbf)[TQ]) {
+  static_assert(LPS == 1 && LB >= 2 && LB + 3 < SLOTS, "one load per slot, and room for the bookkeeping slots");
+  int rdA = 0, rdB = 0;                   // ring stages the current step reads
+  const char *sA_next = s_ring, *sB_next = s_ring + SA * A_STAGE;
+  constexpr int W0 = LB >= 3 ? LB - 3 : 0;  // first bookkeeping slot
+  auto slot_work = [&](auto fast_tag, int slot) __attribute__((always_inline)) {
+    constexpr bool FAST = decltype(fast_tag)::value;
+    // pool feed: cursor, then stage and destination, then (general code) tensor and offset: ready before slot LB
+    if (slot == W0) {
+      if (FAST) bump(fa); else move_cursor(fa);
+    }
+    if (slot == (LB >= 3 ? W0 + 1 : W0)) {
+      next_stage(fa, SA);
+      prepare_dst(fa, ringA, A_STAGE);
+    }
+    if (slot == LB - 1 && !FAST) prepare_src(fa, srdAk, srdAv);
+    // query feed, for the loads of the next step
+    if (slot == LB) {
+      if (FAST) bump(fb); else move_cursor(fb);
+    }
+    if (slot == LB + (LB >= 3 ? 1 : 0)) {
+      next_stage(fb, SB);
+      prepare_dst(fb, ringB, B_STAGE);
+    }
+    if (slot == LB + (LB >= 3 ? 2 : 1) && !FAST) prepare_src(fb, srdBk, srdBv);
+    if (slot == LB + (LB >= 3 ? 3 : 2)) {
+      rdA = (rdA + 1 == SA) ? 0 : rdA + 1;
+      rdB = (rdB + 1 == SB) ? 0 : rdB + 1;
+      sA_next = s_ring + rdA * A_STAGE;
+      sB_next = s_ring + SA * A_STAGE + rdB * B_STAGE;
+    }
+  };
+  auto batch = [&](auto fast_tag, const uint4 (&af)[TP], const uint4 (&bf)[TQ], int b, const char* sA, const char* sB,
+                   int kk, uint4 (&naf)[TP], uint4 (&nbf)[TQ]) __attribute__((always_inline)) {
     const uint32_t c = (((uint32_t)(2 * kk) + (uint32_t)(lane >> 5)) ^ sw) * 16;
-    constexpr int JD = TQ > 1 ? TQ / 2 - 1 : 0;  // the refill loads follow this instruction of the row
+    constexpr int JD = TQ > 1 ? TQ / 2 - 1 : 0;  // the refill load follows this instruction of the row ...
+    constexpr int JW = TQ > 2 ? JD + 1 : JD;     // ... the bookkeeping the next one, where the row has a gap to spare
 #pragma unroll
     for (int i = 0; i < TP; ++i) {
 #pragma unroll
@@ -349,6 +414,10 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
           }
           __builtin_amdgcn_sched_barrier(0);
         }
+        if (j == JW) {
+          slot_work(fast_tag, b * TP + i);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         if (j == TQ - 1 && i < TQ) nbf[i < TQ ? i : 0] = *reinterpret_cast<const uint4*>(sB + fragB + i * 32 * kRowBytes + c);
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -361,12 +430,12 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 #pragma unroll
     for (int j = 0; j < TQ; ++j) fwB[j] = make_uint4(0, 0, 0, 0);
   };
-  auto compute = [&](const char* sA, const char* sB) {
+  auto compute = [&](auto fast_tag, const char* sA, const char* sB) __attribute__((always_inline)) {
     uint4 fa0[TP], fb0[TQ], fa1[TP], fb1[TQ];
-    batch(fwA, fwB, 0, sA, sB, 0, fa0, fb0);  // previous step's sub-step 3 (zeros at the start of a phase); reads sub-step 0
-    batch(fa0, fb0, 1, sA, sB, 1, fa1, fb1);
-    batch(fa1, fb1, 2, sA, sB, 2, fa0, fb0);
-    batch(fa0, fb0, 3, sA, sB, 3, fwA, fwB);  // sub-step 3 is multiplied in the next step
+    batch(fast_tag, fwA, fwB, 0, sA, sB, 0, fa0, fb0);  // previous step's sub-step 3 (zeros at the start of a phase); reads sub-step 0
+    batch(fast_tag, fa0, fb0, 1, sA, sB, 1, fa1, fb1);
+    batch(fast_tag, fa1, fb1, 2, sA, sB, 2, fa0, fb0);
+    batch(fast_tag, fa0, fb0, 3, sA, sB, 3, fwA, fwB);  // sub-step 3 is multiplied in the next step
   };
   // multiply what is still pending (end of a phase); no refills ride on these instructions
   auto drain = [&]() {
@@ -543,34 +612,44 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // the stages the barrier has just freed (query slice of the next step, pool slice of the step
   // after).  The query loads are issued before the pool loads, so "at most LA loads outstanding"
   // means exactly: everything but the newest pool slice has landed.
-  // prologue: query slice 0, pool slices 0 and 1; then the feeds point at query slice 1, pool slice 2
+  // prologue: query slice 0, pool slices 0 and 1.  It leaves the query feed prepared for slice 1 (the
+  // loads of step 0) and the pool feed on slice 1: the slots of step 0 move it on to slice 2.
   auto prologue = [&]() {
     prepare(fb, srdBk, srdBv, ringB, B_STAGE);
 #pragma unroll
     for (int i = 0; i < LB; ++i) dmaB(i);
     next(fb, SB);
-    for (int k = 0; k < 2; ++k) {
-      prepare(fa, srdAk, srdAv, ringA, A_STAGE);
+    prepare(fb, srdBk, srdBv, ringB, B_STAGE);
+    prepare(fa, srdAk, srdAv, ringA, A_STAGE);
 #pragma unroll
-      for (int i = 0; i < LA; ++i) dmaA(i);
-      next(fa, SA);
-    }
+    for (int i = 0; i < LA; ++i) dmaA(i);
+    next(fa, SA);
+    prepare(fa, srdAk, srdAv, ringA, A_STAGE);
+#pragma unroll
+    for (int i = 0; i < LA; ++i) dmaA(i);
+    rdA = rdB = 0;
+    sA_next = s_ring;
+    sB_next = s_ring + SA * A_STAGE;
   };
   prologue();
-  int rdA = 0, rdB = 0;
-  auto run_phase = [&]() {
+  auto step = [&](auto fast_tag) __attribute__((always_inline)) {
+    const char *sA = sA_next, *sB = sB_next;
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LA) : "memory");  // all but the newest pool slice landed
+    __syncthreads();  // ... for every wave, and the stages read in the previous step are free
+    compute(fast_tag, sA, sB);
+  };
+  auto run_phase = [&]() __attribute__((always_inline)) {
     clear_pending();
-    for (int u = 0; u < sps; ++u) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LA) : "memory");  // all but the newest pool slice landed
-      __syncthreads();  // ... for every wave, and the stages read in the previous step are free
-      prepare(fb, srdBk, srdBv, ringB, B_STAGE);
-      prepare(fa, srdAk, srdAv, ringA, A_STAGE);
-      compute(s_ring + rdA * A_STAGE, s_ring + SA * A_STAGE + rdB * B_STAGE);
-      next(fb, SB);
-      next(fa, SA);
-      rdA = (rdA + 1 == SA) ? 0 : rdA + 1;
-      rdB = (rdB + 1 == SB) ? 0 : rdB + 1;
-    }
+    // the accumulators enter the loops in their accumulation registers: without this the code of the
+    // phase end before (the rescale and its loads) is scheduled into the first loop, waits included
+#pragma unroll
+    for (int i = 0; i < TP; ++i)
+#pragma unroll
+      for (int j = 0; j < TQ; ++j) asm volatile("" : "+a"(acc[i][j]));
+    int u = 0;
+    // step u loads pool slice u + 2 and query slice u + 1 of the phase: inside the phase up to u = sps - 3
+    for (; u + 2 < sps; ++u) step(std::true_type{});
+    for (; u < sps; ++u) step(std::false_type{});
     drain();
   };
   if (MODE == 0) {
@@ -608,13 +687,12 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
       set_layer_norms();
       fa = Feed{{0, 0}, 0, srdAk, 0, 0};
       fb = Feed{{0, 0}, 0, srdBk, 0, 0};
-      rdA = rdB = 0;
       prologue();
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus refills of the last steps have landed
 
-  if (MODE == 2) return;  // the sums of this group's layers are in place, tile by tile in register order
+  if (MODE == 2) continue;  // the sums of this group's layers are in place, tile by tile in register order
 
   if (SHARES) {
     // this share of the tile's scores (MODE 4: the score of head `split`), in register order like
@@ -643,7 +721,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-    return;
+    continue;
   }
 
   // ---- tile epilogue: scores, dead/tail masking, top-2 per query column
@@ -715,6 +793,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     }
     p.part[((long long)l * p.npt + pt) * p.Q + q0 + tid] = t;
   }
+  }  // next tile of this workgroup
 #endif
 }
 
@@ -890,6 +969,12 @@ inline int compute_units() {
     cached_cus = cus;
   }
   return cached_cus;
+}
+// Workgroups of a tile-kernel launch: one per compute unit (the kernel's 160 KB of LDS allow no more), a multiple
+// of the 8 XCDs so that a workgroup's virtual indices keep their XCD; never more than there are virtual workgroups.
+inline unsigned launch_grid(unsigned vgrid) {
+  const int cus = compute_units() / 8 * 8;
+  return (cus > 0 && (unsigned)cus < vgrid) ? (unsigned)cus : vgrid;
 }
 constexpr int kStaggerUnit = 6;  // x 1024 clocks per tile index, one to two pipeline steps (flat optimum between 3 and 8)
 
@@ -1078,7 +1163,8 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.stagger_wgs = 0;
     mp.stagger_unit = 0;
     const int64_t per_round = 8LL * mp.chunk;
-    const unsigned grid = (unsigned)(((mp.total + per_round - 1) / per_round) * per_round);
+    mp.vgrid = (int)(((mp.total + per_round - 1) / per_round) * per_round);
+    const unsigned grid = launch_grid((unsigned)mp.vgrid);
     const bool heads = mode == RC_SCORE_PER_HEAD_ALL;
     if (qdesc->dtype == RC_BF16) {
       if (heads)
@@ -1131,7 +1217,8 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.stagger_wgs = compute_units();
     mp.stagger_unit = kStaggerUnit;
     const int64_t per_round = 8LL * mp.chunk;
-    const unsigned grid = (unsigned)(((total + per_round - 1) / per_round) * per_round);
+    mp.vgrid = (int)(((total + per_round - 1) / per_round) * per_round);
+    const unsigned grid = launch_grid((unsigned)mp.vgrid);
     if (qdesc->dtype == RC_BF16)
       launch_tiles<true>(mode, mp, grid, st);
     else
@@ -1222,7 +1309,8 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     mp.stagger_wgs = compute_units();
     mp.stagger_unit = kStaggerUnit;
     const int64_t per_round = 8LL * mp.chunk;
-    const unsigned grid = (unsigned)(((total + per_round - 1) / per_round) * per_round);
+    mp.vgrid = (int)(((total + per_round - 1) / per_round) * per_round);
+    const unsigned grid = launch_grid((unsigned)mp.vgrid);
     if (qdesc->dtype == RC_BF16)
       match_tile_kernel<true, kBlockTile.bp, kBlockTile.bq, 2><<<grid, kThreads, 0, st>>>(mp);
     else
