@@ -4,7 +4,8 @@ The oracle cannot score a whole workload in reasonable time, so each test combin
   (1) every query of every layer: the score the GPU reports must be the oracle's score of the
       block the GPU picked (one from-scratch pair score per query),
   (2) properties that follow from how the inputs were planted (which queries must match what),
-  (3) sampled layers / query ranges: the full oracle search, compared by the ambiguity rule,
+  (3) the first, a middle and the last layer, 128 queries each: the full oracle search over the whole pool,
+      compared by the ambiguity rule (bit-exact index and decision outside the reported near-ties),
   (4) the remap on all layers against the oracle remap fed with the GPU's decisions (bit-exact).
 Needs a real MI355X and its 288 GB.
 """
@@ -73,6 +74,7 @@ def check_sampled_search(oracle, w, pr, gpu, layers, queries):
     rep = []
     for l in layers:
         qs = slice(queries[0], queries[1])
+        say(f"{w.name}: oracle search, layer {l}, queries {queries[0]}..{queries[1] - 1}")
         a = [synth.bits(pr[n][l:l + 1][:, qs]) if n[1] == "q" else synth.bits(pr[n][l:l + 1]) for n in ("kq", "vq", "kp", "vp")]
         orc = oracle.match(dcode(w), w.mode, *a, pr["live"][l:l + 1].cpu().numpy(), w.tau, want_scores=True)
         g = {k: v[l:l + 1, qs] for k, v in gpu.items()}
@@ -91,6 +93,10 @@ def check_remap_all_layers(oracle, w, pr, gpu, remap):
         t = remap["tables"][l]
         t = t[t >= 0]
         assert (remap["refcount"][l][t] >= 1).all()
+
+
+def brief(rep):
+    return [{k: v for k, v in r.items() if k != "ambiguous_list"} for r in rep]
 
 
 def expected_planted_matches(w, plan):
@@ -122,10 +128,14 @@ def test_cfg3_full(oracle):
     say(f"{w.name} full size: L={w.L} P={w.P} Q={w.Q} bf16")
     pr = synth.make_problem(w, DEV)
     gpu, remap, _ = run_path(w, pr)
-    worst = check_reported_scores(oracle, w, pr, gpu, (0, 21, 42, 63))
-    rep = check_sampled_search(oracle, w, pr, gpu, (0, 63), (0, 48)) + check_sampled_search(oracle, w, pr, gpu, (31,), (976, 1024))
-    say(f"{w.name}: worst reported-score error {worst:.2e}; sampled {rep}")
-    assert sum(r["near_tie"] for r in rep) > 0          # near-ties are the point of this workload
+    worst = check_reported_scores(oracle, w, pr, gpu, range(w.L))
+    rep = (check_sampled_search(oracle, w, pr, gpu, (0,), (0, 128)) + check_sampled_search(oracle, w, pr, gpu, (31,), (448, 576))
+           + check_sampled_search(oracle, w, pr, gpu, (63,), (896, 1024)))
+    say(f"{w.name}: worst reported-score error {worst:.2e}; sampled {brief(rep)}")
+    assert sum(r["near_tie"] for r in rep) > 0          # near-ties are the point of this workload ...
+    # ... and still a good share of the sampled queries has a clear winner, for which index and decision must be bit-exact
+    clear = sum(r["n"] - r["ambiguous"] for r in rep)
+    assert clear >= 0.3 * sum(r["n"] for r in rep), f"only {clear} of the sampled queries are outside the near-tie band"
     check_remap_all_layers(oracle, w, pr, gpu, remap)
 
 
@@ -137,9 +147,11 @@ def test_cfg5_full(oracle):
     plan = pr["plan"]
     want = expected_planted_matches(w, plan)
     assert (gpu["match_idx"] == want[None]).all()      # untouched heads score exactly 1, noisy ones ~0.995
-    worst = check_reported_scores(oracle, w, pr, gpu, (0, 15, 31))
-    rep = check_sampled_search(oracle, w, pr, gpu, (0, 31), (0, 40)) + check_sampled_search(oracle, w, pr, gpu, (16,), (472, 512))
-    say(f"{w.name}: worst reported-score error {worst:.2e}; sampled {rep}")
+    worst = check_reported_scores(oracle, w, pr, gpu, (0, 7, 15, 23, 31))
+    rep = (check_sampled_search(oracle, w, pr, gpu, (0,), (0, 128)) + check_sampled_search(oracle, w, pr, gpu, (16,), (192, 320))
+           + check_sampled_search(oracle, w, pr, gpu, (31,), (384, 512)))
+    say(f"{w.name}: worst reported-score error {worst:.2e}; sampled {brief(rep)}")
+    assert sum(r["n"] - r["ambiguous"] for r in rep) >= 0.5 * sum(r["n"] for r in rep)
     check_remap_all_layers(oracle, w, pr, gpu, remap)
 
 
@@ -147,8 +159,8 @@ def test_cfg4_full(oracle):
     w = synth.WORKLOADS[4]
     free, total = torch.cuda.mem_get_info()
     need = w.L * (w.P + w.Q) * w.block_bytes + (24 << 30)
-    if free < need:
-        pytest.skip(f"needs {need >> 30} GiB of free HBM, {free >> 30} GiB available")
+    # an MI355X has 288 GB: too little free memory means something else holds it, which is a failure, not a skip
+    assert free >= need, f"needs {need >> 30} GiB of free HBM, {free >> 30} GiB available"
     say(f"{w.name} full size: L={w.L} P={w.P} Q={w.Q} ({need >> 30} GiB)")
     pr = synth.make_problem(w, DEV)
     gpu, remap, _ = run_path(w, pr)
@@ -158,9 +170,11 @@ def test_cfg4_full(oracle):
     assert (gpu["match_idx"] == want[None]).all()
     dead_plants = plan.planted_slots[plan.live[plan.planted_targets] == 0]
     assert dead_plants.size > 0 and (gpu["best_score"][:, dead_plants] < 0.2).all()
-    worst = check_reported_scores(oracle, w, pr, gpu, (0, 63))
-    rep = check_sampled_search(oracle, w, pr, gpu, (17,), (0, 24)) + check_sampled_search(oracle, w, pr, gpu, (63,), (1000, 1024))
-    say(f"{w.name}: worst reported-score error {worst:.2e}; sampled {rep}")
+    worst = check_reported_scores(oracle, w, pr, gpu, (0, 16, 32, 48, 63))
+    rep = (check_sampled_search(oracle, w, pr, gpu, (0,), (0, 128)) + check_sampled_search(oracle, w, pr, gpu, (32,), (448, 576))
+           + check_sampled_search(oracle, w, pr, gpu, (63,), (896, 1024)))
+    say(f"{w.name}: worst reported-score error {worst:.2e}; sampled {brief(rep)}")
+    assert sum(r["n"] - r["ambiguous"] for r in rep) >= 0.5 * sum(r["n"] for r in rep)
     check_remap_all_layers(oracle, w, pr, gpu, remap)
     # dead pool blocks are never a table target
     t = remap["tables"][5]
