@@ -113,10 +113,12 @@ size_t rc_match_workspace_size(const rc_kv_desc* qdesc, int32_t mode, int64_t Q,
  *   workspace       DEVICE, >= rc_match_workspace_size() bytes, 16-byte aligned; contents
  *                   are scratch.  Calls that share a workspace must not overlap.
  * Accumulation is fp32 on the matrix cores, the epilogue is fp32.  In RC_SCORE_PER_HEAD_ALL
- * mode with more than 256 tiles of 256 x 256 blocks the running minimum over heads is held as
- * 16-bit fixed point (score * 32767 rounded to nearest), so reported scores are then multiples
- * of 1/32767 (error <= 1.6e-5; an exact duplicate still scores exactly 1); smaller problems
- * keep fp32 throughout.  Q == 0 launches nothing; P == 0 writes -1 / -inf.
+ * mode every head's score is rounded to the nearest multiple of 1/32767 before the minimum over
+ * heads is taken (the running minimum is held as 16-bit fixed point next to the accumulators), so
+ * reported scores of that mode are multiples of 1/32767 (error <= 1.6e-5; an exact duplicate still
+ * scores exactly 1; pairs closer than that tie and go to the lower index).  The same pair reports
+ * the same bits whatever the number of layers or tiles of the call.
+ * Q == 0 launches nothing; P == 0 writes -1 / -inf.
  */
 rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_t mode,
                           const void* kq, const void* vq, int64_t Q,

@@ -38,6 +38,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+
+// Two scores in [-1, 1] onto the grid of 1/32767 (signed normalised 16 bit, round to nearest).  The
+// per-head-all mode keeps its minimum over heads on this grid; both of its paths call this.
+__device__ __forceinline__ i16x2 quantise_pair(float a, float b) { return __builtin_amdgcn_cvt_pknorm_i16(a, b); }
 
 constexpr int kBK = 64;             // reduction elements per pipeline step
 constexpr int kRowBytes = kBK * 2;  // bytes of one block's slice in LDS (one 128-byte line)
@@ -494,22 +499,44 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // rows of accumulator register group g (4 registers) of row tile i: wp*WTP + i*32 + 8*g + 4*(lane/32) + 0..3
   auto row_of = [&](int i, int g) { return wp * WTP + i * 32 + 8 * g + 4 * (lane >> 5); };
 
+  // The scale factors of a whole row tile (its four register groups).  The phase ends and the
+  // epilogue walk the row tiles and ask for the factors of row tile i + 1 before they work on row
+  // tile i: asked for group by group, every group paid a memory round trip of its own with nothing
+  // to do meanwhile (16 per phase end; in per-head mode, with 16 phase ends per tile, a fifth of
+  // the launch).
+  struct RowScales {
+    f32x4 rp[4], fp[4];
+  };
+  auto row_scales = [&](int i, int head, RowScales& r) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) pool_scales(row_of(i, g), head, r.rp[g], r.fp[g]);
+  };
+  // walk the row tiles with the factors of the next one in flight: body(i, factors of row tile i)
+  auto for_row_tiles = [&](int head, auto&& body) __attribute__((always_inline)) {
+    RowScales cur, nxt;
+    row_scales(0, head, cur);
+#pragma unroll
+    for (int i = 0; i < TP; ++i) {
+      if (i + 1 < TP) row_scales(i + 1, head, nxt);
+      __builtin_amdgcn_sched_barrier(0);
+      body(i, cur);
+      __builtin_amdgcn_sched_barrier(0);
+      cur = nxt;
+    }
+  };
+
   // acc <- acc * (rq * rp)   (end of a K phase)
   auto rescale = [&](int head) {
     float rq[TQ], fq[TQ];
     query_scales(head, rq, fq);
+    for_row_tiles(head, [&](int i, const RowScales& rs) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < TP; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 rp, fp;
-        pool_scales(row_of(i, g), head, rp, fp);
+      for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] *= rq[j] * rp[e];
-        __builtin_amdgcn_sched_barrier(0);  // one register group at a time keeps the pressure low
-      }
+          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] *= rq[j] * rs.rp[g][e];
+    });
   };
 
   // per-head mode: running minimum over heads of the finished head score; acc restarts at 0.
@@ -526,33 +553,25 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 #pragma unroll
         for (int r = 0; r < 8; ++r) smin[SM ? i : 0][SM ? j : 0][r] = 0x7fff7fff;
   }
-  typedef short i16x2 __attribute__((ext_vector_type(2)));
   auto finish_head = [&](int head) {
     float rq[TQ], fq[TQ];
     query_scales(head, rq, fq);
+    for_row_tiles(head, [&](int i, const RowScales& rs) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < TP; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 rp, fp;
-        pool_scales(row_of(i, g), head, rp, fp);
+      for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
           for (int e = 0; e < 4; e += 2) {
-            const float s0 = acc[i][j][4 * g + e] * (fq[j] * fp[e]), s1 = acc[i][j][4 * g + e + 1] * (fq[j] * fp[e + 1]);
-            // |score| <= 1 up to rounding; the clamp keeps the conversion inside 16 bits
-            const int q0 = (int)rintf(fminf(fmaxf(s0, -1.f), 1.f) * 32767.f), q1 = (int)rintf(fminf(fmaxf(s1, -1.f), 1.f) * 32767.f);
-            const i16x2 nw = {(short)q0, (short)q1};
+            const float s0 = acc[i][j][4 * g + e] * (fq[j] * rs.fp[g][e]), s1 = acc[i][j][4 * g + e + 1] * (fq[j] * rs.fp[g][e + 1]);
+            // the hardware's conversion to signed normalised 16 bit: clamp to [-1, 1], times 32767, round to nearest
+            const i16x2 nw = quantise_pair(s0, s1);
             int& slot = smin[SM ? i : 0][SM ? j : 0][2 * g + (e >> 1)];
-            const i16x2 old = __builtin_bit_cast(i16x2, slot);
-            const i16x2 mn = {old[0] < nw[0] ? old[0] : nw[0], old[1] < nw[1] ? old[1] : nw[1]};
-            slot = __builtin_bit_cast(int, mn);
+            slot = __builtin_bit_cast(int, __builtin_elementwise_min(__builtin_bit_cast(i16x2, slot), nw));
             acc[i][j][4 * g + e] = 0.f;
             acc[i][j][4 * g + e + 1] = 0.f;
           }
-        __builtin_amdgcn_sched_barrier(0);
-      }
+    });
   };
 
   // layer-mean mode: when a phase (the K or the V tensor of one layer) ends, the accumulators hold
@@ -702,25 +721,21 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     query_scales(head, rq, fq);
     const long long tile_lin = (((long long)lz * p.S + split) * p.npt + pt) * p.nqt + qt;
     f32x4* out = reinterpret_cast<f32x4*>(p.dpart) + tile_lin * (BP * BQ / 4) + (long long)wave * (TP * 4 * TQ * 64) + lane;
+    for_row_tiles(head, [&](int i, const RowScales& rs) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < TP; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 rp, fp;
-        pool_scales(row_of(i, g), head, rp, fp);
+      for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
           f32x4 d;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             // fq fp = aVq aVp / 2; rq rp = (aKq aKp) / (aVq aVp); in MODE 4 the K part was rescaled at the phase end
-            const float f = (MODE == 4 || split_v) ? fq[j] * fp[e] : (rq[j] * fq[j]) * (rp[e] * fp[e]);
+            const float f = (MODE == 4 || split_v) ? fq[j] * rs.fp[g][e] : (rq[j] * fq[j]) * (rs.rp[g][e] * rs.fp[g][e]);
             d[e] = acc[i][j][4 * g + e] * f;
           }
           out[((i * 4 + g) * TQ + j) * 64] = d;
         }
-        __builtin_amdgcn_sched_barrier(0);
-      }
+    });
     continue;
   }
 
@@ -736,31 +751,50 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   {
     float rq[TQ], fq[TQ];
     if (MODE == 0) query_scales(0, rq, fq);
+    // dead blocks and rows past the end of the pool: -inf.  The flags of row tile i + 1 are asked for
+    // with its scale factors, before the work on row tile i.
+    struct RowBias {
+      f32x4 b[4];
+    };
+    auto row_bias = [&](int i, RowBias& r) {
 #pragma unroll
-    for (int i = 0; i < TP; ++i)
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int gp = p0 + row_of(i, g) + e;
+          r.b[g][e] = (gp < p.P && (!p.live || p.live[(long long)l * p.P + gp])) ? 0.f : -INFINITY;
+        }
+    };
+    RowScales cur, nxt;
+    RowBias bcur, bnxt;
+    if (MODE == 0) row_scales(0, 0, cur);
+    row_bias(0, bcur);
+#pragma unroll
+    for (int i = 0; i < TP; ++i) {
+      if (i + 1 < TP) {
+        if (MODE == 0) row_scales(i + 1, 0, nxt);
+        row_bias(i + 1, bnxt);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int row = row_of(i, g);
-        f32x4 rp, fp, bias;
-        if (MODE == 0) pool_scales(row, 0, rp, fp);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int gp = p0 + row + e;
-          bias[e] = (gp < p.P && (!p.live || p.live[(long long)l * p.P + gp])) ? 0.f : -INFINITY;
-        }
 #pragma unroll
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             float sc;
             if (MODE == 0)
-              sc = acc[i][j][4 * g + e] * (fq[j] * fp[e]) + bias[e];
+              sc = acc[i][j][4 * g + e] * (fq[j] * cur.fp[g][e]) + bcur.b[g][e];
             else
-              sc = (float)__builtin_bit_cast(i16x2, smin[SM ? i : 0][SM ? j : 0][2 * g + (e >> 1)])[e & 1] / 32767.f + bias[e];
+              sc = (float)__builtin_bit_cast(i16x2, smin[SM ? i : 0][SM ? j : 0][2 * g + (e >> 1)])[e & 1] / 32767.f + bcur.b[g][e];
             top2_push(sc, p0 + row + e, best[j], bidx[j], second[j]);
           }
-        __builtin_amdgcn_sched_barrier(0);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      cur = nxt;
+      bcur = bnxt;
+    }
   }
   // the two half-waves hold interleaved rows of the same columns
 #pragma unroll
@@ -858,12 +892,20 @@ __global__ __launch_bounds__(256) void tile_sums_select_kernel(const float* __re
       const float* src = dpart + ((long long)(r >> 8) * nqt + (q >> 8)) * 65536 + sum_index(r & 255, q & 255);
       f32x4 sum = {0.f, 0.f, 0.f, 0.f};  // groups are added in ascending order: the same bits on every run
       if (take_min) {
-        sum = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src));
-        for (int g = 1; g < groups; ++g) {
+        // per-head-all score: every head's score goes onto the grid of 1/32767 first, exactly as the
+        // whole-tile path keeps its running minimum, so that a pair reports the same bits on both paths
+        int qmin[4] = {32767, 32767, 32767, 32767};
+        for (int g = 0; g < groups; ++g) {
           const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + g * gstride));
 #pragma unroll
-          for (int e = 0; e < 4; ++e) sum[e] = fminf(sum[e], v[e]);
+          for (int e = 0; e < 4; e += 2) {
+            const i16x2 q = quantise_pair(v[e], v[e + 1]);
+            qmin[e] = min(qmin[e], (int)q[0]);
+            qmin[e + 1] = min(qmin[e + 1], (int)q[1]);
+          }
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum[e] = (float)qmin[e] / 32767.f;
       } else {
         int g = 0;
         for (; g + 4 <= groups; g += 4) {

@@ -222,6 +222,26 @@ def test_per_head_many_layers_whole_tiles(oracle):
     full_check(oracle, w, pr, live)
 
 
+def test_per_head_scores_do_not_depend_on_the_path():
+    # the same layer scored inside a call of 90 layers (whole tiles, running minimum in 16-bit fixed point) and in a
+    # call of its own (one share per head, minimum taken by the selection kernel): identical bits, identical picks
+    w = synth.scaled(synth.WORKLOADS[5], name="perhead_paths", L=90, P=513, Q=40, T=16, R=2, E=300, seed=16)
+    say(w.name)
+    pr = synth.make_problem(w, DEV)
+    many, _ = run_gpu_match(pr, w, pr["live"])
+    for l in (0, 37, 89):
+        one = {n: pr[n][l:l + 1] for n in ("kq", "vq", "kp", "vp")}
+        alone, _ = run_gpu_match(one, synth.scaled(w, L=1), pr["live"][l:l + 1])
+        for k in ("best_score", "second_score"):
+            assert np.array_equal(many[k][l].view(np.uint32), alone[k][0].view(np.uint32)), (l, k)
+        for k in ("best_idx", "match_idx"):
+            assert np.array_equal(many[k][l], alone[k][0]), (l, k)
+        # multiples of 1/32767
+        assert np.array_equal(np.round(many["best_score"][l].astype(np.float64) * 32767) / 32767,
+                              many["best_score"][l].astype(np.float64).round(12)) or \
+            np.abs(np.round(many["best_score"][l].astype(np.float64) * 32767) / 32767 - many["best_score"][l]).max() < 1e-7
+
+
 def test_per_head_T16_H4(oracle):
     w = synth.scaled(synth.WORKLOADS[5], name="perhead_T16_H4", L=1, P=130, Q=33, T=16, H=4, R=1, E=163, seed=14)
     say(w.name)
