@@ -304,10 +304,12 @@ def assert_remap_equal(g, o):
 @pytest.mark.parametrize("in_place", [False, True])
 def test_remap_random(oracle, in_place):
     rng = np.random.RandomState(17)
-    for case in range(8):
+    # small and large id ranges (decided in LDS / through global memory), tables of one and of several workgroups
+    # per layer (counts finalized by the gathering workgroup / by a launch of its own), many small layers
+    for case in range(10):
         L, P, Q, R, E = [(3, 40, 12, 5, 30), (2, 3000, 700, 9, 1031), (1, 50, 1, 1, 7), (4, 10, 64, 3, 4099),
                          (1, 5000, 2000, 64, 300), (2, 17, 9, 2, 1), (2, 20000, 8192, 8, 5003),
-                         (1, 70000, 4500, 16, 4100)][case]
+                         (1, 70000, 4500, 16, 4100), (1, 3000, 700, 40, 2000), (130, 50, 20, 2, 33)][case]
         say(f"remap random case {case} L={L} P={P} Q={Q} R={R} E={E} in_place={in_place}")
         NB = P + Q + 5
         ids = rng.permutation(NB)
@@ -337,6 +339,21 @@ def test_remap_all_to_one_target(oracle):
     g = gpu_remap(tables, qids, None, match, P, NB, refcount)
     assert_remap_equal(g, o)
     assert g["refcount"][0, 5] == 1 + 2 * Q and g["freed"].all()
+
+
+def test_remap_every_entry_is_rewritten(oracle):
+    # whole batches in which every entry names a matched query block: the list of a batch's hits is full
+    say("remap: 40000 entries, all of them references to matched query blocks")
+    rng = np.random.RandomState(23)
+    P, Q, NB = 8, 4096, 8 + 4096
+    qids = (P + rng.permutation(Q)).astype(np.int32)
+    tables = qids[rng.randint(0, Q, size=(2, 1, 40000))].astype(np.int32)
+    refcount = np.stack([np.bincount(t.ravel(), minlength=NB) for t in tables]).astype(np.int32)
+    match = rng.randint(0, P, size=(2, Q)).astype(np.int32)
+    o = oracle.remap(tables, qids, None, match, P, NB, refcount)
+    g = gpu_remap(tables, qids, None, match, P, NB, refcount)
+    assert_remap_equal(g, o)
+    assert int(g["n_remapped"].sum()) == 80000 and g["freed"].all()
 
 
 def test_remap_cfg4_tables_all_layers(oracle):
