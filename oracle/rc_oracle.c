@@ -21,6 +21,8 @@
  *     block shared by all layers, match iff distance <= threshold;
  *   - the percentile threshold of the warm-up distances (nearest rank);
  *   - admission of unmatched query blocks into free pool slots, with their cached norms;
+ *   - room for the admissions of a step: unreferenced blocks leave the pool, least recently used first,
+ *     with the block metadata (last use, reference counts) the paper keeps per block;
  *   - block-table remap with reference counts (Sec. IV-B).
  *
  * Pins (tests/test_oracle_pins.py): bit decode against two library decoders,
@@ -541,6 +543,63 @@ int rc_oracle_pool_admit(int L, int64_t block_elems, int nh,
     ++count;
   }
   *n_admitted = count;
+  return 0;
+}
+
+/*
+ * Block metadata update (Sec. IV-A keeps per-block metadata with an LRU order, i.e. a record of when a
+ * block was last used): value goes to array[slots[i]] for every listed slot inside [0, P).  Entries
+ * outside that range (-1 = "no slot") are skipped.
+ */
+int rc_oracle_pool_touch(const int32_t* slots, int64_t n, int32_t value, int32_t* array, int64_t P) {
+  if (n < 0 || P < 0 || (n > 0 && !slots) || (P > 0 && !array)) return 1;
+  for (int64_t i = 0; i < n; ++i)
+    if (slots[i] >= 0 && slots[i] < P) array[slots[i]] = value;
+  return 0;
+}
+
+/*
+ * References that the engine drops (a request has ended; Sec. IV-B: a block goes back to the free pool
+ * only when its reference count reaches 0): every listed id inside [0, NB) loses one reference, once per
+ * time it is listed.
+ */
+int rc_oracle_refcount_release(const int32_t* ids, int64_t n, int32_t* refcount, int64_t NB) {
+  if (n < 0 || NB < 0 || (n > 0 && !ids) || (NB > 0 && !refcount)) return 1;
+  for (int64_t i = 0; i < n; ++i)
+    if (ids[i] >= 0 && ids[i] < NB) refcount[ids[i]] -= 1;
+  return 0;
+}
+
+/*
+ * Room for the admissions of a step (Sec. IV-B: the evictor returns a block to the free pool only at
+ * reference count 0; Sec. IV-A: block metadata is kept in LRU order).
+ *   wanted = number of unmatched queries (match_idx[q] < 0) + extra_wanted;
+ *   free   = number of slots that are not live.
+ * While free < wanted, the live slot that nobody references (refcount[p] == 0; any live slot when refcount
+ * is NULL) and that was used least recently (smallest last_used, equal values by lowest slot number) leaves
+ * the pool (live = 0).  Referenced slots never leave; when the unreferenced ones run out the loop stops.
+ */
+int rc_oracle_pool_evict(int64_t P, uint8_t* live, const int32_t* refcount, const int32_t* last_used,
+                         const int32_t* match_idx, int64_t Q, int64_t extra_wanted, int32_t* n_free,
+                         int32_t* n_evicted) {
+  if (P < 0 || Q < 0 || extra_wanted < 0 || !n_free || !n_evicted) return 1;
+  if ((P > 0 && (!live || !last_used)) || (Q > 0 && !match_idx)) return 1;
+  int64_t wanted = extra_wanted, free_slots = 0, evicted = 0;
+  for (int64_t q = 0; q < Q; ++q) wanted += match_idx[q] < 0;
+  for (int64_t p = 0; p < P; ++p) free_slots += !live[p];
+  while (free_slots < wanted) {
+    int64_t victim = -1;
+    for (int64_t p = 0; p < P; ++p) {
+      if (!live[p] || (refcount && refcount[p] != 0)) continue;
+      if (victim < 0 || last_used[p] < last_used[victim]) victim = p; /* strict: the lowest slot wins a tie */
+    }
+    if (victim < 0) break;
+    live[victim] = 0;
+    ++free_slots;
+    ++evicted;
+  }
+  *n_free = (int32_t)free_slots;
+  *n_evicted = (int32_t)evicted;
   return 0;
 }
 

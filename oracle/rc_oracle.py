@@ -279,6 +279,42 @@ def pool_admit(kq, vq, q_ksq, q_vsq, kp, vp, p_ksq, p_vsq, live, match_idx):
     return slot, int(n[0])
 
 
+def pool_touch(slots, value, array):
+    """array[slots[i]] = value for the listed slots inside the array (IN PLACE, int32)."""
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    assert array.dtype == np.int32 and array.flags.c_contiguous and array.ndim == 1
+    _check(_load().rc_oracle_pool_touch(_p(slots), ctypes.c_int64(slots.size), ctypes.c_int32(int(value)), _p(array),
+                                        ctypes.c_int64(array.size)), "pool_touch")
+    return array
+
+
+def refcount_release(ids, refcount):
+    """refcount[ids[i]] -= 1 for every listed id inside the array, with multiplicity (IN PLACE, int32)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    assert refcount.dtype == np.int32 and refcount.flags.c_contiguous and refcount.ndim == 1
+    _check(_load().rc_oracle_refcount_release(_p(ids), ctypes.c_int64(ids.size), _p(refcount),
+                                              ctypes.c_int64(refcount.size)), "refcount_release")
+    return refcount
+
+
+def pool_evict(live, refcount, last_used, match_idx, extra_wanted=0):
+    """Make room for the unmatched queries (+ extra_wanted): unreferenced live slots leave in LRU order.
+    live (uint8 [P]) is updated IN PLACE; refcount may be None.  Returns (n_free, n_evicted)."""
+    assert live.dtype == np.uint8 and live.flags.c_contiguous and live.ndim == 1
+    P = live.size
+    if refcount is not None:
+        refcount = np.ascontiguousarray(refcount, dtype=np.int32)
+        assert refcount.shape == (P,)
+    last_used = np.ascontiguousarray(last_used, dtype=np.int32)
+    assert last_used.shape == (P,)
+    match_idx = np.ascontiguousarray(match_idx, dtype=np.int32)
+    nf, ne = np.zeros(1, dtype=np.int32), np.zeros(1, dtype=np.int32)
+    _check(_load().rc_oracle_pool_evict(ctypes.c_int64(P), _p(live), _p(refcount), _p(last_used), _p(match_idx),
+                                        ctypes.c_int64(match_idx.size), ctypes.c_int64(int(extra_wanted)), _p(nf), _p(ne)),
+           "pool_evict")
+    return int(nf[0]), int(ne[0])
+
+
 def remap(tables, query_ids, pool_ids, match_idx, P, NB, refcount):
     """Block-table remap.  Returns dict(tables, refcount, freed, n_remapped); inputs are not modified."""
     tables = np.ascontiguousarray(tables, dtype=np.int32)

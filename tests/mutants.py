@@ -38,6 +38,17 @@ MUTANTS = [
     ("remap_out_of_range_entry_clamped", "      } else {\n        tout[e] = b;\n      }", "      } else {\n        tout[e] = -1;\n      }", 0),
     ("norm_head_filter_inverted", "if (head >= 0 && h != head) continue;", "if (head >= 0 && h == head) continue;", 0),
     ("dot_head_filter_dropped", "if (head >= 0 && h != head) continue;", "", 1),
+    ("touch_out_of_range_clamped", "if (slots[i] >= 0 && slots[i] < P) array[slots[i]] = value;",
+     "array[slots[i] < 0 ? 0 : slots[i] >= P ? P - 1 : slots[i]] = value;", 0),
+    ("release_without_multiplicity", "if (ids[i] >= 0 && ids[i] < NB) refcount[ids[i]] -= 1;",
+     "if (ids[i] >= 0 && ids[i] < NB && (i == 0 || ids[i] != ids[i - 1])) refcount[ids[i]] -= 1;", 0),
+    ("evict_referenced_slots_too", "if (!live[p] || (refcount && refcount[p] != 0)) continue;", "if (!live[p]) continue;", 0),
+    ("evict_most_recently_used", "last_used[p] < last_used[victim]", "last_used[p] > last_used[victim]", 0),
+    ("evict_tie_to_highest_slot", "last_used[p] < last_used[victim]", "last_used[p] <= last_used[victim]", 0),
+    ("evict_ignores_free_slots", "for (int64_t p = 0; p < P; ++p) free_slots += !live[p];", "", 0),
+    ("evict_counts_matched_queries", "wanted += match_idx[q] < 0;", "wanted += 1;", 0),
+    ("evict_extra_wanted_dropped", "int64_t wanted = extra_wanted, free_slots = 0, evicted = 0;",
+     "int64_t wanted = 0, free_slots = 0, evicted = 0;", 0),
     ("norm_not_squared", "acc += a * a;", "acc += fabs(a);", 0),
     ("cosine_without_sqrt", "return xy / sqrt(xx * yy);", "return xy / (xx * yy);", 0),
     ("cosine_zero_norm_and", "if (xx == 0.0 || yy == 0.0) return 0.0;", "if (xx == 0.0 && yy == 0.0) return 0.0;", 0),

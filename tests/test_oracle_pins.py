@@ -670,3 +670,77 @@ def test_candidate_distances_vs_matrix_and_rules(oracle):
     for order in ([2, 1, 0], [1, 0, 2], [0, 2, 1]):
         r = oracle.candidate_distances(0, kq, vq, kp2, vp2, np.tile(np.array([order], dtype=np.int32), (Q, 1)), None, 1e9)
         assert (r["best_idx"] == 0).all(), order
+
+
+# ---- pool metadata and eviction (Sec. IV-B: free at reference count 0; Sec. IV-A: LRU order on block metadata)
+
+def test_pool_touch_and_release_hand_cases(oracle):
+    stamp = np.array([5, 5, 5, 5, 5], dtype=np.int32)
+    oracle.pool_touch(np.array([3, -1, 0, 7, 3], dtype=np.int32), 9, stamp)      # -1 and 7 are outside: skipped
+    assert stamp.tolist() == [9, 5, 5, 9, 5]
+    rc = np.array([2, 1, 0, 3], dtype=np.int32)
+    oracle.refcount_release(np.array([0, 3, 3, -1, 9, 0], dtype=np.int32), rc)   # with multiplicity
+    assert rc.tolist() == [0, 1, 0, 1]
+
+
+def test_pool_evict_hand_cases(oracle):
+    U = np.array([-1, -1, -1], dtype=np.int32)          # three unmatched queries
+    # slots:            0  1  2  3  4  5
+    live = np.array([1, 1, 0, 1, 1, 1], dtype=np.uint8)
+    refc = np.array([0, 2, 0, 0, 0, 1], dtype=np.int32)
+    used = np.array([7, 1, 0, 4, 4, 0], dtype=np.int32)
+    # one slot is free already; two more are needed: the unreferenced ones are 0, 3, 4 with stamps 7, 4, 4:
+    # slots 3 and 4 go (stamp 4 before 7); slot 1 (stamp 1) and slot 5 (stamp 0) are referenced and stay
+    lv = live.copy()
+    assert oracle.pool_evict(lv, refc, used, U) == (3, 2)
+    assert lv.tolist() == [1, 1, 0, 0, 0, 1]
+    # one more needed than there are candidates: all three unreferenced slots go, and that is all
+    lv = live.copy()
+    assert oracle.pool_evict(lv, refc, used, U, extra_wanted=2) == (4, 3)
+    assert lv.tolist() == [0, 1, 0, 0, 0, 1]
+    # ties go to the lowest slot: only one of the two stamp-4 slots is needed
+    lv = live.copy()
+    assert oracle.pool_evict(lv, refc, used, np.array([-1, 5, -1], dtype=np.int32)) == (2, 1)
+    assert lv.tolist() == [1, 1, 0, 0, 1, 1]
+    # without reference counts every live slot is a candidate: stamps 0 (slot 5), 1 (slot 1) go first
+    lv = live.copy()
+    assert oracle.pool_evict(lv, None, used, U) == (3, 2)
+    assert lv.tolist() == [1, 0, 0, 1, 1, 0]
+    # enough room already, or nothing unmatched: untouched
+    lv = live.copy()
+    assert oracle.pool_evict(lv, refc, used, np.array([-1, 2], dtype=np.int32)) == (1, 0) and np.array_equal(lv, live)
+    assert oracle.pool_evict(lv, refc, used, np.array([0, 2], dtype=np.int32)) == (1, 0) and np.array_equal(lv, live)
+    # empty pool
+    assert oracle.pool_evict(np.zeros(0, np.uint8), None, np.zeros(0, np.int32), U) == (0, 0)
+
+
+def test_pool_evict_vs_sorting_and_invariants(oracle):
+    rng = np.random.RandomState(31)
+    for case in range(40):
+        P = int(rng.choice([1, 2, 17, 64, 300, 1500]))
+        live = (rng.rand(P) < rng.choice([0.5, 0.9, 1.0])).astype(np.uint8)
+        refc = (rng.randint(0, 3, P) * (rng.rand(P) < 0.6)).astype(np.int32)
+        used = rng.randint(0, rng.choice([2, 5, 1000]), P).astype(np.int32)     # few distinct stamps: many ties
+        m = np.where(rng.rand(int(rng.randint(0, 2 * P + 2))) < 0.6, -1, 0).astype(np.int32)
+        extra = int(rng.randint(0, 3))
+        use_rc = rng.rand() < 0.7
+        lv = live.copy()
+        n_free, n_ev = oracle.pool_evict(lv, refc if use_rc else None, used, m, extra)
+        # the same by sorting the candidates by (stamp, slot), written with a library sort
+        wanted = int((m < 0).sum()) + extra
+        free0 = int((live == 0).sum())
+        cand = np.flatnonzero((live == 1) & ((refc == 0) if use_rc else True))
+        order = cand[np.lexsort((cand, used[cand]))]
+        k = min(max(wanted - free0, 0), order.size)
+        want = live.copy()
+        want[order[:k]] = 0
+        assert np.array_equal(lv, want), case
+        assert (n_free, n_ev) == (free0 + k, k)
+        # invariants: nothing referenced left, nothing dead came back, survivors are not older than victims
+        gone = np.flatnonzero((live == 1) & (lv == 0))
+        if use_rc:
+            assert (refc[gone] == 0).all()
+        assert (lv <= live).all()
+        stay = np.setdiff1d(cand, gone)
+        if gone.size and stay.size:
+            assert used[gone].max() <= used[stay].min()
