@@ -331,13 +331,14 @@ def run_extras(args, w, pr, kernels, s):
     torch.cuda.empty_cache()
     stream_bytes = args.streaming * L * Q * w.block_bytes + (4 << 30)   # the steps' inputs plus temporaries while drawing them
     if args.streaming > 0 and w.mode == 0 and P >= (args.streaming + 1) * Q and torch.cuda.mem_get_info()[0] > stream_bytes + (8 << 30):
-        # the paper's steady state (not the timed step above): consecutive decoding steps over one pool with the
-        # paper's own measure.  Per step: norms of the new blocks, layer-mean search, decision against a threshold
-        # that lives on the device, remap of a layer-shared table, admission of the blocks that found no partner.
+        # the paper's steady state (not the timed step above): consecutive decoding steps over a pool that is FULL,
+        # with the paper's own measure.  Per step: norms of the new blocks, layer-mean search, decision against a
+        # threshold that lives on the device, remap of a layer-shared table with reference counts, last-use stamps of
+        # the partners, the references of the requests that end at this step are dropped, the unreferenced blocks
+        # leave the pool in LRU order to make room, admission of the blocks that found no partner, their metadata.
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         S = args.streaming
-        lv = pr["live"].min(dim=0).values.contiguous().clone()
-        lv[P - S * Q:] = 0                                            # room for S steps of admissions
+        lv = torch.ones(P, dtype=torch.uint8, device=dev)            # every slot holds a resident block
         thr_dev = torch.full((1,), 0.5, dtype=torch.float32, device=dev)
         gen = torch.Generator(device=dev)
         gen.manual_seed(4242)
@@ -346,7 +347,7 @@ def run_extras(args, w, pr, kernels, s):
         for sidx in range(S):                                         # inputs of every step, built before the clock starts
             kq_s = torch.empty_like(pr["kq"])
             vq_s = torch.empty_like(pr["vq"])
-            tgt = torch.randint(0, P - S * Q, (n_copy,), generator=gen, device=dev)
+            tgt = torch.randint(S * Q, P, (n_copy,), generator=gen, device=dev)   # copies of blocks that stay referenced
             for l in range(L):                                        # layer by layer: the fp32 temporaries stay small
                 kq_s[l] = torch.randn(pr["kq"].shape[1:], generator=gen, device=dev, dtype=torch.float32).to(pr["kq"].dtype)
                 vq_s[l] = torch.randn(pr["vq"].shape[1:], generator=gen, device=dev, dtype=torch.float32).to(pr["vq"].dtype)
@@ -359,10 +360,16 @@ def run_extras(args, w, pr, kernels, s):
         ws_rm2 = torch.empty(rc.rc_remap_workspace_size(1, 1, Q, Q, P + Q), dtype=torch.uint8, device=dev)
         table = (P + torch.arange(Q, dtype=torch.int32, device=dev)).reshape(1, 1, Q).contiguous()
         qids = (P + torch.arange(Q, dtype=torch.int32, device=dev)).contiguous()
-        refc = torch.ones((1, P + Q), dtype=torch.int32, device=dev)
-        lm2, ad2, rm2 = None, None, None
+        refc = torch.ones((1, P + Q), dtype=torch.int32, device=dev)  # every resident block is referenced once
+        refc_out = torch.empty_like(refc)
+        stamp = torch.zeros(P, dtype=torch.int32, device=dev)
+        # the requests that end at step s hold the blocks of slots [s*Q, (s+1)*Q)
+        ending = [torch.arange(sidx * Q, (sidx + 1) * Q, dtype=torch.int32, device=dev) for sidx in range(S)]
+        lm2, ad2, ev2 = None, None, None
+        rm2 = dict(tables=torch.empty_like(table), refcount=refc_out, freed=torch.empty((1, Q), dtype=torch.uint8, device=dev),
+                   n_remapped=torch.empty((1,), dtype=torch.int32, device=dev))
         dec = torch.empty((Q,), dtype=torch.int32, device=dev)
-        shared, admitted = [], []
+        shared, admitted, evicted = [], [], []
         torch.cuda.synchronize()
         e0.record()
         for sidx in range(S):
@@ -370,18 +377,30 @@ def run_extras(args, w, pr, kernels, s):
             lm2 = rc.rc_match_blocks_layer_mean(steps_kq[sidx], steps_vq[sidx], qk, qv, pr["kp"], pr["vp"], pk, pv, lv,
                                                 float("inf"), workspace=ws_lm2, out=lm2)
             rc.rc_apply_threshold(lm2["best_idx"], lm2["best_dist"], thr_dev, dec)
-            rm2 = rc.rc_remap_block_table(table, qids, None, dec.reshape(1, Q), P, P + Q, refc, workspace=ws_rm2, out=rm2)
+            rc.rc_remap_block_table(table, qids, None, dec.reshape(1, Q), P, P + Q, refc, workspace=ws_rm2, out=rm2)
+            pool_refc = refc_out[0, :P]                                # (a view: the first P counts are the pool's slots)
+            rc.rc_pool_touch(dec, sidx + 1, stamp)
+            rc.rc_refcount_release(ending[sidx], pool_refc)
+            ev2 = rc.rc_pool_evict(lv, pool_refc, stamp, dec, out=ev2)
             ad2 = rc.rc_pool_admit(steps_kq[sidx], steps_vq[sidx], qk, qv, pr["kp"], pr["vp"], pk, pv, lv, dec,
                                    workspace=ws_ad2, out=ad2)
+            rc.rc_pool_touch(ad2["slot_of_query"], sidx + 1, stamp)
+            rc.rc_pool_touch(ad2["slot_of_query"], 1, pool_refc)
+            refc[0, :P].copy_(pool_refc)                               # the counts carry over; the new ids start at 1 again
             shared.append((dec >= 0).sum())
             admitted.append(ad2["n_admitted"].clone())
+            evicted.append(ev2["n_evicted"].clone())
         e1.record()
         torch.cuda.synchronize()
         st_ms = e0.elapsed_time(e1) / S
         streaming = {"steps": S, "ms_per_step": st_ms, "pairs_per_s": pairs / (st_ms * 1e-3),
+                     "pool": "full: every slot live and referenced; the requests that end free Q blocks per step",
                      "shared_per_step": [int(x.item()) for x in shared],
+                     "evicted_per_step": [int(x.item()) for x in evicted],
                      "admitted_per_step": [int(x.item()) for x in admitted],
-                     "what": "norms(Q) + layer-mean search + device-threshold decision + layer-shared remap + admission"}
+                     "live_slots_at_the_end": int(lv.sum().item()), "pool_slots": P,
+                     "what": "norms(Q) + layer-mean search + device-threshold decision + layer-shared remap + last-use stamps + "
+                             "release of ended requests + LRU eviction of unreferenced blocks + admission"}
     return streaming
 
 

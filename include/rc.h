@@ -342,6 +342,44 @@ rc_status rc_pool_admit(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_
                         int32_t* slot_of_query, int32_t* n_admitted,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Block metadata update (Sec. IV-A: per-block metadata is kept in LRU order, i.e. with a record of when
+ * the block was last used): array[slots[i]] = value for every listed slot inside [0, P); entries outside
+ * (-1 = "no slot", as rc_pool_admit and the search write them) are skipped.  Used with the step number as
+ * value on the last-use stamps of the matched and of the admitted slots, and with 1 on the reference
+ * counts of the admitted slots.  All pointers DEVICE; n == 0 launches nothing.
+ */
+rc_status rc_pool_touch(const int32_t* slots, int64_t n, int32_t value, int32_t* array, int64_t P, void* hip_stream);
+
+/*
+ * References that the engine drops, e.g. the table entries of a request that has ended (Sec. IV-B: a
+ * block returns to the free pool only when its reference count reaches 0): refcount[ids[i]] -= 1 for
+ * every listed id inside [0, NB), once per time it is listed (integer atomics: the same counts whatever
+ * the order).  All pointers DEVICE; n == 0 launches nothing.
+ */
+rc_status rc_refcount_release(const int32_t* ids, int64_t n, int32_t* refcount, int64_t NB, void* hip_stream);
+
+/*
+ * Room for the admissions of a step (Sec. IV-B: the evictor returns a block to the free pool only at
+ * reference count 0; Sec. IV-A: block metadata in LRU order).  wanted = number of unmatched queries
+ * (match_idx[q] < 0) + extra_wanted; free = number of slots that are not live.  If free < wanted, live
+ * slots that nobody references (refcount[p] == 0; every live slot when refcount is NULL) leave the pool
+ * (pool_live = 0), least recently used first (smallest last_used, equal values by lowest slot number),
+ * until free == wanted or none is left.  Referenced slots never leave: a pool of referenced blocks only
+ * stays full, and rc_pool_admit then leaves the surplus queries out.  Call it before rc_pool_admit.
+ *
+ *   pool_live       DEVICE uint8 [P], updated in place
+ *   refcount        DEVICE int32 [P] or NULL (references held on each slot, e.g. the first P entries of a
+ *                   layer-shared refcount array of rc_remap_block_table with identity pool ids)
+ *   last_used       DEVICE int32 [P], any monotone stamp (e.g. the step number), see rc_pool_touch
+ *   match_idx       DEVICE int32 [Q], the step's decisions
+ *   n_free          DEVICE int32 [1]: free slots afterwards;  n_evicted: DEVICE int32 [1]
+ * One workgroup walks the metadata (9 bytes per slot) seven times; no workspace.  The same slots on every run.
+ */
+rc_status rc_pool_evict(int64_t P, uint8_t* pool_live, const int32_t* refcount, const int32_t* last_used,
+                        const int32_t* match_idx, int64_t Q, int64_t extra_wanted,
+                        int32_t* n_free, int32_t* n_evicted, void* hip_stream);
+
 /* HOST string describing the calling thread's last error ("" if none). Never NULL. */
 const char* rc_last_error(void);
 

@@ -19,7 +19,8 @@ RC_SCORE_BLOCK, RC_SCORE_PER_HEAD_ALL = 0, 1
 EXPORTS = ("rc_block_norms", "rc_match_workspace_size", "rc_match_blocks", "rc_remap_workspace_size",
            "rc_remap_block_table", "rc_remap_static_scratch_size", "rc_remap_block_table_static", "rc_score_candidates", "rc_layer_mean_workspace_size", "rc_match_blocks_layer_mean",
            "rc_pat_workspace_size", "rc_pat_threshold", "rc_apply_threshold", "rc_pool_admit_workspace_size", "rc_pool_admit",
-           "rc_candidate_distances_workspace_size", "rc_candidate_distances", "rc_last_error", "rc_version")
+           "rc_candidate_distances_workspace_size", "rc_candidate_distances", "rc_pool_touch", "rc_refcount_release", "rc_pool_evict",
+           "rc_last_error", "rc_version")
 
 
 class RcError(RuntimeError):
@@ -84,6 +85,12 @@ def lib():
         L.rc_candidate_distances_workspace_size.restype = sz
         L.rc_candidate_distances.argtypes = [dp, dp, vp, vp, i64, vp, vp, i64, vp, vp, i64, f32, vp, vp, vp, vp, vp, sz, vp]
         L.rc_candidate_distances.restype = i32
+        L.rc_pool_touch.argtypes = [vp, i64, i32, vp, i64, vp]
+        L.rc_pool_touch.restype = i32
+        L.rc_refcount_release.argtypes = [vp, i64, vp, i64, vp]
+        L.rc_refcount_release.restype = i32
+        L.rc_pool_evict.argtypes = [i64, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        L.rc_pool_evict.restype = i32
         L.rc_last_error.restype = ctypes.c_char_p
         L.rc_version.restype = i32
         _lib = L
@@ -351,4 +358,39 @@ def rc_candidate_distances(kq, vq, kp, vp, pool_live, cand, threshold, workspace
                                         _ptr(pool_live), _ptr(cand), C, float(threshold), _ptr(out["dist"]),
                                         _ptr(out["best_idx"]), _ptr(out["best_dist"]), _ptr(out["match_idx"]),
                                         _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def rc_pool_touch(slots, value, array):
+    """array[slots[i]] = value for the listed slots inside the array (in place; int32 device tensors)."""
+    _dev(slots, array)
+    assert slots.dtype == torch.int32 and array.dtype == torch.int32 and slots.is_contiguous() and array.is_contiguous()
+    _check(lib().rc_pool_touch(_ptr(slots), slots.numel(), int(value), _ptr(array), array.numel(), _stream()))
+    return array
+
+
+def rc_refcount_release(ids, refcount):
+    """refcount[ids[i]] -= 1 for every listed id inside the array, with multiplicity (in place)."""
+    _dev(ids, refcount)
+    assert ids.dtype == torch.int32 and refcount.dtype == torch.int32 and ids.is_contiguous() and refcount.is_contiguous()
+    _check(lib().rc_refcount_release(_ptr(ids), ids.numel(), _ptr(refcount), refcount.numel(), _stream()))
+    return refcount
+
+
+def rc_pool_evict(pool_live, refcount, last_used, match_idx, extra_wanted=0, out=None):
+    """Make room for the step's unmatched queries: unreferenced live slots leave in LRU order (pool_live in place).
+
+    Returns dict(n_free int32 [1], n_evicted int32 [1]) on the device."""
+    _dev(pool_live, refcount, last_used, match_idx)
+    P = pool_live.numel()
+    assert pool_live.dtype == torch.uint8 and pool_live.is_contiguous()
+    assert last_used.dtype == torch.int32 and last_used.is_contiguous() and last_used.numel() == P
+    if refcount is not None:
+        assert refcount.dtype == torch.int32 and refcount.is_contiguous() and refcount.numel() == P
+    assert match_idx.dtype == torch.int32 and match_idx.is_contiguous()
+    if out is None:
+        out = dict(n_free=torch.empty(1, dtype=torch.int32, device=pool_live.device),
+                   n_evicted=torch.empty(1, dtype=torch.int32, device=pool_live.device))
+    _check(lib().rc_pool_evict(P, _ptr(pool_live), _ptr(refcount), _ptr(last_used), _ptr(match_idx), match_idx.numel(),
+                               int(extra_wanted), _ptr(out["n_free"]), _ptr(out["n_evicted"]), _stream()))
     return out

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librc.so")
-SOURCES = ["rc_norms.hip", "rc_match.hip", "rc_remap.hip", "rc_candidates.hip", "rc_pat.hip", "rc_pool.hip"]
+SOURCES = ["rc_norms.hip", "rc_match.hip", "rc_remap.hip", "rc_candidates.hip", "rc_pat.hip", "rc_pool.hip", "rc_evict.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
