@@ -48,6 +48,8 @@ constexpr int kBK = 64;             // reduction elements per pipeline step
 constexpr int kRowBytes = kBK * 2;  // bytes of one block's slice in LDS (one 128-byte line)
 constexpr int kPoolWaves = 2, kQueryWaves = 2;  // waves of a workgroup along the two tile sides
 constexpr int kThreads = 64 * kPoolWaves * kQueryWaves;
+constexpr int kMaxGrid = 512;                          // workgroups of a tile-kernel launch, at most
+constexpr int kScheduleHeader = (8 + kMaxGrid) * 32;   // ints ahead of the claim words of a dynamic tile schedule
 constexpr int kPoolStages = 3, kQueryStages = 2;
 
 // Partial selection result of one pool tile for one query.
@@ -70,6 +72,12 @@ struct MatchParams {
   int npt, nqt;
   int total;  // L * npt * nqt (layer-mean mode: groups * npt * nqt)
   int vgrid;  // virtual workgroups: total rounded up to whole rounds of 8 XCDs x chunk; the launch walks them
+  int* ctr;        // nullptr = a fixed schedule; else zero at launch: 8 counters of slots taken from a list's back, one
+                   // progress word per workgroup (each on 128 bytes of its own), then from [kScheduleHeader] on the
+                   // claim words, `rounds` of them per workgroup
+  int rounds;      // slots in one workgroup's walk
+  int dyn_from;    // slots from this one on can be taken from the back of their list
+  int steal_min;   // a slot is taken from a list's back only if its own workgroup is at least this far short of it
   int chunk;  // tiles handed to one XCD in a row
   int G;      // layer-mean mode: layers per group (one workgroup walks the layers of its group)
   int S;      // split mode: workgroups per tile, each over its own part of the reduction (even)
@@ -191,17 +199,104 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   __shared__ __attribute__((aligned(1024))) char s_ring[RING];
   const uint32_t ringA = lds_offset(s_ring), ringB = ringA + SA * A_STAGE;
 
-  // ---- which tiles: the launch has one workgroup per compute unit, and workgroup b walks the
-  // virtual workgroups b, b + gridDim.x, ... of a grid of p.vgrid (a fixed schedule; measured
-  // against one workgroup per tile it is neither faster nor slower).  Consecutive runs of `chunk`
-  // tiles go to one XCD (workgroups are dealt round-robin to the 8 XCDs and gridDim.x is a multiple
-  // of 8, so a workgroup stays on its XCD's tiles), so tiles that share operands share an L2.
-  for (int wg = blockIdx.x; wg < p.vgrid; wg += gridDim.x) {
+  // ---- which tiles: the launch has one workgroup per compute unit, each walks tiles of a grid of
+  // p.vgrid virtual workgroups.  Virtual workgroup v belongs to XCD v & 7, and consecutive runs of
+  // `chunk` tiles go to one XCD, so tiles that share operands share an L2.  The virtual workgroups form 8
+  // lists, one per XCD, of p.vgrid / 8 slots each; workgroup b walks list b & 7 from slot b >> 3 in strides
+  // of gridDim.x / 8.  With a fixed schedule (p.ctr == nullptr) that is all.
+  // The XCDs of one chip run this kernel at clocks of their own (measured: 8 % between the fastest and the
+  // slowest on one box), so with many rounds the fast ones would idle at the end.  Then every slot has a claim
+  // word, and a workgroup owns a slot only once it has swapped that word from 0 to 1.  The walk stays as it is
+  // (the workgroups that share a pool tile keep running side by side and find each other's slices in the L2:
+  // handing tiles out in order of arrival costs 3 % with several query tiles), but a workgroup that is through
+  // with it takes slots from the BACK of the list whose workgroups are furthest behind.  A tile taken that way
+  // ends a whole tile time later, so it is taken only if the workgroup whose walk contains it is at least
+  // p.steal_min slots short of it (every workgroup publishes the slot it works on).  A walk skips what was
+  // taken.  All of this is words that one workgroup writes or swaps at a time, on cache lines of their own:
+  // counters that all workgroups add to cost more than the scheme gains.  Which workgroup computes a tile does
+  // not change the tile's result.
+  const bool dynamic = p.ctr != nullptr;
+  const int nslots = p.vgrid >> 3;
+  const int my_list = blockIdx.x & 7, my_pos = blockIdx.x >> 3, stride = gridDim.x >> 3;
+  // the claim words of one workgroup's walk lie together: [list][position][round]
+  auto claim_of = [&](int list, int slot) { return p.ctr + kScheduleHeader + (list * stride + slot % stride) * p.rounds + slot / stride; };
+  auto progress_of = [&](int list, int pos) { return p.ctr + (8 + list * stride + pos) * 32; };
+  auto taken_of = [&](int list) { return p.ctr + list * 32; };
+  // Thread 0 keeps the walk: my_slot, and what its claim word held before this workgroup's swap (0 = the slot
+  // is this workgroup's).  The swap for the next slot of the walk goes out when a tile's last phase ends and is
+  // looked at after the tile's epilogue, so nobody waits for it (and no steady-state loop runs with its answer
+  // pending).
+  int my_slot = my_pos, prev = 1;
+  bool walking = dynamic && my_slot < nslots, home_tile = false;
+  // slots ahead of p.dyn_from are never taken from the back and need no claim
+  auto claim = [&](int slot) { return slot < p.dyn_from ? 0 : atomicExch(claim_of(my_list, slot), 1); };
+  if (walking && threadIdx.x == 0) prev = claim(my_slot);
+  auto claim_next = [&]() __attribute__((always_inline)) {
+    if (dynamic && threadIdx.x == 0 && home_tile) {
+      my_slot += stride;
+      walking = my_slot < nslots;
+      prev = 1;
+      if (walking) prev = claim(my_slot);
+    }
+  };
+  for (int round = 0;; ++round) {
   // every wave is done with the ring (last fragments, epilogue scratch) before the next tile's loads land in it
-  if (wg != (int)blockIdx.x) __syncthreads();
+  if (round) __syncthreads();
+  int wg;
+  if (dynamic) {
+    volatile int* box = reinterpret_cast<volatile int*>(s_ring);  // the ring is free between tiles
+    if (threadIdx.x == 0) {
+      int slot = -1, list = my_list;
+      while (walking && prev != 0) {  // taken from the back by another workgroup: on to the next slot of the walk
+        my_slot += stride;
+        walking = my_slot < nslots;
+        if (walking) prev = claim(my_slot);
+      }
+      home_tile = walking;
+      if (walking) {
+        slot = my_slot;
+        if (slot + 2 * stride >= p.dyn_from)
+          __hip_atomic_store(progress_of(my_list, my_pos), slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        unsigned closed = 1u << my_list;
+        for (int tries = 0; tries < 16 && slot < 0; ++tries) {
+          int least = 0x7fffffff;
+          list = -1;
+          for (int x = 0; x < 8; ++x) {
+            if (closed >> x & 1) continue;
+            const int at = __hip_atomic_load(progress_of(x, my_pos), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (at < least) { least = at; list = x; }
+          }
+          if (list < 0) break;
+          const int from_back = nslots - 1 - atomicAdd(taken_of(list), 1);
+          const int at = from_back < p.dyn_from ? 0x7fffffff
+                                       : __hip_atomic_load(progress_of(list, from_back % stride), __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+          if (from_back < p.dyn_from || from_back - at < p.steal_min)
+            closed |= 1u << list;  // the list's own workgroups are about to reach its back
+          else if (atomicExch(claim_of(list, from_back), 1) == 0)
+            slot = from_back;
+        }
+      }
+      box[0] = slot;
+      box[1] = list;
+    }
+    __syncthreads();
+    const int slot_d = __builtin_amdgcn_readfirstlane(box[0]);
+    const int list_d = __builtin_amdgcn_readfirstlane(box[1]);
+    __syncthreads();
+    if (slot_d < 0) break;  // nothing left that is worth taking
+    wg = slot_d * 8 + list_d;
+  } else {
+    wg = blockIdx.x + round * gridDim.x;
+    if (wg >= p.vgrid) break;
+  }
   const int slot = wg >> 3;
   const int tile = ((slot / p.chunk) * 8 + (wg & 7)) * p.chunk + slot % p.chunk;
-  if (tile >= p.total) continue;
+  if (tile >= p.total) {
+    claim_next();
+    continue;
+  }
   const int split = SHARES ? tile % p.S : 0;   // which share of the tile (MODE 3: part of the reduction, MODE 4: head)
   const int tile_id = SHARES ? tile / p.S : tile;
   const int qt = tile_id % p.nqt;
@@ -220,7 +315,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // closely); later rounds inherit the spread.  Nothing else changes.  Measured on one box against
   // an unspread start: 3 % faster with one query tile (Q = 256), 5 % in per-head mode (Q = 512),
   // within 0.5 % with four query tiles (Q = 1024).
-  if (wg == (int)blockIdx.x && wg < p.stagger_wgs)
+  if (round == 0 && (int)blockIdx.x < p.stagger_wgs)
     for (int i = 0; i < (((slot % p.chunk) / p.nqt) & 15) * p.stagger_unit; ++i) __builtin_amdgcn_s_sleep(16);
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -710,6 +805,7 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus refills of the last steps have landed
+  claim_next();
 
   if (MODE == 2) continue;  // the sums of this group's layers are in place, tile by tile in register order
 
@@ -1015,8 +1111,42 @@ inline int compute_units() {
 // Workgroups of a tile-kernel launch: one per compute unit (the kernel's 160 KB of LDS allow no more), a multiple
 // of the 8 XCDs so that a workgroup's virtual indices keep their XCD; never more than there are virtual workgroups.
 inline unsigned launch_grid(unsigned vgrid) {
-  const int cus = compute_units() / 8 * 8;
+  int cus = compute_units() / 8 * 8;
+  if (cus > kMaxGrid) cus = kMaxGrid;
   return (cus > 0 && (unsigned)cus < vgrid) ? (unsigned)cus : vgrid;
+}
+// What a launch of more than one round keeps behind the rest of the workspace: the header (counters and progress
+// words, 128 bytes each) and one claim word per slot of every workgroup's walk.
+constexpr int kChunk = 32;
+constexpr int kStealMin = 64;
+constexpr int kTailShare = 10;   // the last tenth of every list can be taken from its back
+constexpr int kDynamicRounds = 16;  // launches of fewer rounds keep the fixed schedule: nothing to gain there
+inline int64_t virtual_grid(int64_t total) { return (total + 8 * kChunk - 1) / (8 * kChunk) * (8 * kChunk); }
+inline size_t schedule_bytes(int64_t total) {
+  // the walks of a launch with fewer workgroups than kMaxGrid are longer; together they never hold more than
+  // one slot per virtual workgroup plus one per workgroup
+  return (size_t)(kScheduleHeader + virtual_grid(total > 0 ? total : 1) + kMaxGrid) * sizeof(int);
+}
+__global__ void clear_schedule_kernel(int* ctr, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) ctr[i] = 0;
+}
+// Sets mp.ctr for a launch of `grid` workgroups over mp.vgrid virtual ones: counters and claims (cleared on the
+// stream) when the launch has many rounds, a fixed schedule otherwise.  Measured on two shapes of 64 and 192
+// rounds: 2 to 3 % less time than the fixed schedule with the last tenth of the lists open to the other XCDs'
+// workgroups; with every slot claimed, 4 % MORE than the fixed schedule (a swap per tile costs that much).
+inline rc_status prepare_schedule(MatchParams& mp, unsigned grid, void* schedule, hipStream_t st) {
+  mp.ctr = nullptr;
+  mp.rounds = 0;
+  mp.steal_min = kStealMin;
+  mp.dyn_from = 0;
+  if ((unsigned)mp.vgrid < kDynamicRounds * grid || !schedule) return RC_OK;
+  mp.ctr = static_cast<int*>(schedule);
+  const int per_list = (int)grid / 8;
+  mp.rounds = (mp.vgrid / 8 + per_list - 1) / per_list;
+  mp.dyn_from = mp.vgrid / 8 - (mp.vgrid / 8) / kTailShare;
+  const int n = kScheduleHeader + (int)grid * mp.rounds;
+  clear_schedule_kernel<<<(n + 1023) / 1024 < 64 ? (n + 1023) / 1024 : 64, 1024, 0, st>>>(mp.ctr, n);
+  return check_launch("rc_match_blocks(tile schedule)");
 }
 constexpr int kStaggerUnit = 6;  // x 1024 clocks per tile index, one to two pipeline steps (flat optimum between 3 and 8)
 
@@ -1134,8 +1264,9 @@ extern "C" size_t rc_match_workspace_size(const rc_kv_desc* qdesc, int32_t mode,
   if (S > 1) return split_layout(S, qdesc->n_layers, P, Q).bytes;
   const TileShape ts = tile_for(mode, Q);
   const int64_t npt = (P + ts.bp - 1) / ts.bp;
+  const int64_t nqt = (Q + ts.bq - 1) / ts.bq;
   const int64_t n = (int64_t)qdesc->n_layers * (npt > 0 ? npt : 1) * Q;
-  return (size_t)(n > 0 ? n : 1) * sizeof(Part);
+  return (size_t)(n > 0 ? n : 1) * sizeof(Part) + schedule_bytes((int64_t)qdesc->n_layers * npt * nqt);
 }
 
 extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* pdesc, int32_t mode, const void* kq,
@@ -1199,14 +1330,17 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.npt = (int)sl.npt;
     mp.nqt = (int)sl.nqt;
     mp.total = (int)(L * sl.npt * sl.nqt * S);
-    mp.chunk = 32;
+    mp.chunk = kChunk;
     mp.G = 1;
     mp.S = S;
     mp.stagger_wgs = 0;
     mp.stagger_unit = 0;
-    const int64_t per_round = 8LL * mp.chunk;
-    mp.vgrid = (int)(((mp.total + per_round - 1) / per_round) * per_round);
+    mp.vgrid = (int)virtual_grid(mp.total);
     const unsigned grid = launch_grid((unsigned)mp.vgrid);
+    mp.ctr = nullptr;
+    mp.rounds = 0;
+    mp.steal_min = 0;
+    mp.dyn_from = 0;
     const bool heads = mode == RC_SCORE_PER_HEAD_ALL;
     if (qdesc->dtype == RC_BF16) {
       if (heads)
@@ -1252,15 +1386,15 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.npt = (int)npt;
     mp.nqt = (int)nqt;
     mp.total = (int)total;
-    mp.chunk = 32;
+    mp.chunk = kChunk;
     mp.dpart = nullptr;
     mp.G = 1;
     mp.S = 1;
     mp.stagger_wgs = compute_units();
     mp.stagger_unit = kStaggerUnit;
-    const int64_t per_round = 8LL * mp.chunk;
-    mp.vgrid = (int)(((total + per_round - 1) / per_round) * per_round);
+    mp.vgrid = (int)virtual_grid(total);
     const unsigned grid = launch_grid((unsigned)mp.vgrid);
+    if (rc_status s = prepare_schedule(mp, grid, static_cast<char*>(workspace) + need - schedule_bytes(total), st)) return s;
     if (qdesc->dtype == RC_BF16)
       launch_tiles<true>(mode, mp, grid, st);
     else
@@ -1345,14 +1479,14 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     mp.npt = (int)npt;
     mp.nqt = (int)nqt;
     mp.total = (int)total;
-    mp.chunk = 32;
+    mp.chunk = kChunk;
     mp.G = ls.G;
     mp.S = 1;
     mp.stagger_wgs = compute_units();
     mp.stagger_unit = kStaggerUnit;
-    const int64_t per_round = 8LL * mp.chunk;
-    mp.vgrid = (int)(((total + per_round - 1) / per_round) * per_round);
+    mp.vgrid = (int)virtual_grid(total);
     const unsigned grid = launch_grid((unsigned)mp.vgrid);
+    if (rc_status s = prepare_schedule(mp, grid, nullptr, st)) return s;  // a group of layers per tile: few, long tiles
     if (qdesc->dtype == RC_BF16)
       match_tile_kernel<true, kBlockTile.bp, kBlockTile.bq, 2><<<grid, kThreads, 0, st>>>(mp);
     else

@@ -69,10 +69,11 @@ def test_match_validation(lib):
                          kw.get("kq", FAKE), FAKE, kw.get("Q", 4), FAKE, FAKE, FAKE, FAKE, kw.get("P", 64), FAKE, FAKE,
                          None, kw.get("tau", 0.9), FAKE, FAKE, FAKE, None, kw.get("ws", FAKE), kw.get("wsb", 1 << 26),
                          None]
-    # more than one round of tiles: one 16-byte partial per (layer, pool tile, query)
+    # whole tiles: one 16-byte partial per (layer, pool tile, query), then the tile schedule: 520 words of 128 bytes and one claim word per tile slot and workgroup
+    # (400 tiles rounded up to whole rounds of 256)
     many = desc(L=200, n=4)
-    assert lib.rc_match_workspace_size(ctypes.byref(many), 0, 4, 257) == 200 * 2 * 4 * 16
-    assert lib.rc_match_workspace_size(ctypes.byref(many), 1, 4, 257) == 200 * 2 * 4 * 16
+    assert lib.rc_match_workspace_size(ctypes.byref(many), 0, 4, 257) == 200 * 2 * 4 * 16 + (520 * 32 + 512 + 512) * 4
+    assert lib.rc_match_workspace_size(ctypes.byref(many), 1, 4, 257) == 200 * 2 * 4 * 16 + (520 * 32 + 512 + 512) * 4
     # per-head mode with few tiles: one share of 256 KB per head and tile, then the partials of the pool chunks
     assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 64) == 2 * 8 * 65536 * 4 + 2 * 2 * 4 * 16
     assert lib.rc_match_workspace_size(ctypes.byref(q), 1, 4, 257) == 2 * 8 * 2 * 65536 * 4 + 2 * 9 * 4 * 16

@@ -128,6 +128,35 @@ def test_match_many_layers_whole_tiles(oracle, L, P, Q):
     assert (gpu["best_idx"][:, 0] == 1).all() and (gpu["match_idx"][:, 0] == 1).all()
 
 
+def test_match_many_rounds_tiles_change_hands(oracle):
+    # 16 rounds of tiles and more: the last tenth of every XCD's list of tiles can be taken over by the workgroups of
+    # the XCDs that are through with theirs.  Every tile must still be computed exactly once: the call equals, bit
+    # for bit, the same layers scored 20 at a time (two rounds, the fixed schedule), and sampled queries equal the
+    # oracle's search.
+    L, P, Q = 260, 513, 1300
+    w = synth.scaled(synth.WORKLOADS[2], name=f"many_rounds_L{L}_{P}x{Q}", L=L, P=P, Q=Q, H=1, planted_frac=0.3, R=1,
+                     E=P + Q, seed=21)
+    say(w.name)
+    pr = synth.make_problem(w, DEV)
+    live = pr["live"].clone()
+    live[:, 9] = 0
+    for rep in range(3):  # who takes which tile differs from run to run
+        whole, _ = run_gpu_match(pr, w, live)
+        for l0 in range(0, L, 20):
+            part = {n: pr[n][l0:l0 + 20] for n in ("kq", "vq", "kp", "vp")}
+            some, _ = run_gpu_match(part, synth.scaled(w, L=20), live[l0:l0 + 20])
+            for k in ("best_idx", "match_idx"):
+                assert np.array_equal(whole[k][l0:l0 + 20], some[k]), (rep, l0, k)
+            for k in ("best_score", "second_score"):
+                assert np.array_equal(whole[k][l0:l0 + 20].view(np.uint32), some[k].view(np.uint32)), (rep, l0, k)
+    layers = [0, 131, 259]
+    queries = np.arange(0, Q, 31)
+    orc = oracle_match(oracle, pr, w, live, layers=layers, queries=queries)
+    sub = {k: whole[k][layers][:, queries] for k in whole}
+    rep = parity.check_match(sub, orc, w.tau, parity.score_lookup(orc["scores"], sub["best_idx"]))
+    say(f"{w.name}: {rep}")
+
+
 def test_match_split_shapes(oracle):
     # the split of the reduction at its extremes: one tile over 64 shares (8 steps each), 128 tiles over 2
     # shares (a whole tensor each), head counts whose step count is not a power of two
