@@ -179,12 +179,20 @@ def run_config(args, w, traffic, extras, cpu_budget):
     flop = pairs * 4.0 * w.D                       # 2 (mul+add) x D x 2 (K and V) per pair
     kv_bytes = L * (P + Q) * w.block_bytes         # every pool and query block read once
     match_tflops = flop / (match_ms * 1e-3) / 1e12
-    roofline = {"kernel": "match_tile_kernel (inside rc_match_blocks)", "bound": "mfma",
-                "achieved": match_tflops, "peak": PEAK_TFLOPS[w.dtype], "unit": "TFLOP/s",
-                "frac": match_tflops / PEAK_TFLOPS[w.dtype],
-                "traffic": traffic.get(w.name) if not args.layers else None,
-                "algorithmic_bytes": kv_bytes, "algorithmic_flop": flop}
     match_gbs = kv_bytes / (match_ms * 1e-3) / 1e9
+    # which roof binds: the launch's FLOP per byte of KV against the ridge of the two peaks (312 FLOP/byte)
+    intensity = flop / kv_bytes if kv_bytes else 0.0
+    ridge = PEAK_TFLOPS[w.dtype] * 1e12 / (PEAK_HBM_GBS * 1e9)
+    roofline = {"kernel": "match_tile_kernel (inside rc_match_blocks)"}
+    if intensity >= ridge:
+        roofline.update(bound="mfma", achieved=match_tflops, peak=PEAK_TFLOPS[w.dtype], unit="TFLOP/s",
+                        frac=match_tflops / PEAK_TFLOPS[w.dtype])
+    else:
+        roofline.update(bound="hbm", achieved=match_gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=match_gbs / PEAK_HBM_GBS)
+    roofline.update(traffic=traffic.get(w.name) if not args.layers else None,
+                    algorithmic_bytes=kv_bytes, algorithmic_flop=flop, flop_per_byte=intensity, ridge_flop_per_byte=ridge,
+                    tflops=match_tflops, mfma_frac=match_tflops / PEAK_TFLOPS[w.dtype],
+                    gb_per_s=match_gbs, hbm_frac=match_gbs / PEAK_HBM_GBS)
     qnorm_bytes = L * Q * w.block_bytes
     remap_bytes = L * (2 * w.R * w.E * 4 + 2 * w.NB * 4)
     kernels = {
@@ -404,6 +412,42 @@ def run_extras(args, w, pr, kernels, s):
     return streaming
 
 
+def mfma_probe():
+    """What this machine sustains on back-to-back fp16 MFMA with random operands and nothing else (the chip lowers its
+    clock under matrix load): TFLOP/s of the last two of three launches of about 0.1 s, and the clock that rate
+    implies (256 CUs x 4 SIMDs x 1024 FLOP per clock)."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "paper_2507_21433_amd", "librc_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError("librc_probe.so is not built: run python -m paper_2507_21433_amd.build")
+    lib = ctypes.CDLL(path)
+    lib.rc_probe_mfma_f16.restype = ctypes.c_int
+    lib.rc_probe_mfma_f16.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+    dev = "cuda:0"
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    operands = torch.randn(16384, generator=gen, device=dev).to(torch.float16).contiguous()   # 32 KiB
+    sink = torch.empty(cus * 256, dtype=torch.float32, device=dev)
+    iters = 300000
+    stream = torch.cuda.current_stream().cuda_stream
+    rates = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        err = lib.rc_probe_mfma_f16(operands.data_ptr(), iters, sink.data_ptr(), cus, stream)
+        if err:
+            raise RuntimeError(f"rc_probe_mfma_f16: hipError {err}")
+        e1.record()
+        torch.cuda.synchronize()
+        rates.append(cus * 4 * iters * 16 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    tflops = (rates[1] + rates[2]) / 2
+    return {"pure_mfma_tflops": tflops, "implied_clock_ghz": tflops * 1e12 / (cus * 4 * 1024) / 1e9,
+            "what": "back-to-back v_mfma_f32_32x32x16_f16, random operands, 4 waves per CU, no memory traffic; "
+                    "three launches of 0.1 s, mean of the last two"}
+
+
 def remap_sweep(args):
     """rc_remap_block_table on the table shape of cfg4 (64 tables of 776 entries per layer, 1024 new blocks, 50 176
     block ids) at growing layer counts, beside a device-to-device copy of the same number of bytes in the same run:
@@ -504,6 +548,11 @@ def main():
                       cpu_budget=0 if args.step_only else args.cpu_pairs)
     if args.remap_sweep and not args.step_only:
         head["kernels"]["rc_remap_block_table"]["sweep"] = remap_sweep(args)
+    if not args.step_only:
+        ceiling = mfma_probe()
+        for b in list(configs.values()) + [head]:
+            r = b["roofline"]
+            r["ceiling"] = dict(ceiling, frac_of_ceiling=r["tflops"] / ceiling["pure_mfma_tflops"])
     brief = {k: head[k] for k in ("value", "unit", "ms_per_step", "dtype", "config", "kv_gb_per_s", "roofline", "cpu_baseline")}
     brief["kernels"] = {k: v for k, v in head["kernels"].items() if "not in the step" not in k or "cold fill" in k}
     configs[head["config"]["workload"]] = brief

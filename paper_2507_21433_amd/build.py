@@ -1,4 +1,5 @@
-"""Build the C-ABI HIP library for gfx950 in-tree (``paper_2507_21433_amd/librc.so``)."""
+"""Build the C-ABI HIP library for gfx950 in-tree (``paper_2507_21433_amd/librc.so``) and, beside it, the
+benchmark's MFMA-rate probe (``librc_probe.so``, a measurement aid that the search library does not contain)."""
 import os
 import subprocess
 import sys
@@ -7,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librc.so")
+PROBE_LIB = os.path.join(HERE, "librc_probe.so")
 SOURCES = ["rc_norms.hip", "rc_match.hip", "rc_remap.hip", "rc_candidates.hip", "rc_pat.hip", "rc_pool.hip", "rc_evict.hip"]
 
 FLAGS = [
@@ -24,6 +26,10 @@ def build(verbose=False):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    probe = [hipcc] + FLAGS + [os.path.join(CSRC, "probe_mfma.hip"), "-o", PROBE_LIB]
+    if verbose:
+        print(" ".join(probe), flush=True)
+    subprocess.check_call(probe)
     return LIB
 
 

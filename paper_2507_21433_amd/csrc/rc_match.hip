@@ -12,10 +12,12 @@
 // Operand slices of 64 elements (128 bytes per block, one L2 line) go global -> LDS with
 // direct-to-LDS 16-byte buffer loads.  With a 256 x 256 tile all of the 160 KB of LDS is ring
 // buffer: three stages for the pool slices (two always in flight) and two for the query slices,
-// which come from the L2.  What bounds the kernel is the rate at which the L2 delivers those
-// slices to the compute units (a pool line that misses costs more than a query line that hits),
-// not HBM and not the matrix cores.  The 16-byte chunks of an LDS row are XOR-swizzled by the row
-// number so that fragment reads spread over all banks.
+// which come from the L2.  In the steady-state loop a matrix instruction is in flight 95 % of
+// the time (a wave issues one instruction every four cycles, a 32x32x16 matrix instruction takes
+// 32, and the loads, LDS reads and bookkeeping of a step are placed in the issue slots between);
+// what bounds the launch then is the clock: under this load the chip runs at about 1.5 GHz, not
+// the 2.4 GHz of its peak figure, and each XCD at a clock of its own.  The 16-byte chunks of an
+// LDS row are XOR-swizzled by the row number so that fragment reads spread over all banks.
 //
 // The same kernel body serves three modes: the cosine score per layer (MODE 0), the same per KV
 // head with the minimum over heads (MODE 1), and the layer-mean Euclidean distance of the
@@ -205,8 +207,10 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
   // lists, one per XCD, of p.vgrid / 8 slots each; workgroup b walks list b & 7 from slot b >> 3 in strides
   // of gridDim.x / 8.  With a fixed schedule (p.ctr == nullptr) that is all.
   // The XCDs of one chip run this kernel at clocks of their own (measured: 8 % between the fastest and the
-  // slowest on one box), so with many rounds the fast ones would idle at the end.  Then every slot has a claim
-  // word, and a workgroup owns a slot only once it has swapped that word from 0 to 1.  The walk stays as it is
+  // slowest on one box), so with many rounds the fast ones would idle at the end.  Then the slots from
+  // p.dyn_from on (the tail of every list) have a claim word each, and a workgroup owns such a slot only once it
+  // has swapped that word from 0 to 1; the slots before are walked as in the fixed schedule (a swap per tile
+  // costs more than the scheme gains: measured 4 % of the launch with every slot claimed).  The walk stays as it is
   // (the workgroups that share a pool tile keep running side by side and find each other's slices in the L2:
   // handing tiles out in order of arrival costs 3 % with several query tiles), but a workgroup that is through
   // with it takes slots from the BACK of the list whose workgroups are furthest behind.  A tile taken that way
