@@ -2,6 +2,8 @@
 
     python3 -m paper_2507_21433_amd.profsum collect --workload 4 --passes A B C D E --dir gpurun_out
     python3 -m paper_2507_21433_amd.profsum summarise --workload 4 --dir gpurun_out --out profiles
+    python3 -m paper_2507_21433_amd.profsum trace --dir gpurun_out --out profiles
+    python3 -m paper_2507_21433_amd.profsum table --json gpurun_out/bench.json --out profiles
 
 ``collect`` runs, once per pass, ``rocprofv3 --pmc <counters of the pass> --kernel-trace --output-format csv
 -d <dir>/pmc_w<N>_<pass> -- python3 bench.py --step-only 1 --workload N --steps 3 --warmup 1`` (one pass per run: the
@@ -10,9 +12,15 @@ this library's kernels and of the device copies.  ``summarise`` turns them into 
 (mean counter values per launch of the tile kernel, the figures derived from them, the commands) and enters the
 workload's HBM traffic into ``profiles/hbm_traffic.json``, which ``bench.py`` reads for ``roofline.traffic``.
 
+``trace`` runs ``rocprofv3 --kernel-trace --stats -- python3 bench.py ...`` on the timed step alone and on the headline
+workload with its side measurements, and writes the per-kernel times of this library's kernels to
+``profiles/bench_kernel_trace.md``; ``table`` condenses the JSON line of a default
+``bench.py`` run into ``profiles/bench_all_workloads.md``.
+
 FETCH_SIZE and WRITE_SIZE are scaled by what the same counters read, in the same run, for the 1 GiB device-to-device
-copy that ``bench.py`` issues before anything else (the largest copy of the run): bytes = counter x (2^30 / counter of
-that copy).
+copy that ``bench.py`` issues before anything else (the first device copy of the run): bytes = counter x (2^30 /
+counter of that copy).  What the counters see is what leaves the L2 for the fabric: reads that the memory-side cache
+serves are in it.
 """
 import argparse
 import csv
@@ -87,7 +95,7 @@ def collect(args):
 
 def read_pass(d):
     """{kernel kind: {counter: [value per dispatch]}}, {kernel kind: [duration ns per dispatch]}, bench JSON or None."""
-    files = glob.glob(os.path.join(d, "*", "*_counter_collection.csv"))
+    files = sorted(glob.glob(os.path.join(d, "*", "*_counter_collection.csv")), key=os.path.getmtime, reverse=True)
     if not files:
         return None
     vals, durs = {}, {}
@@ -206,8 +214,10 @@ def summarise(args):
     traffic = None
     if "D" in found and "E" in found:
         f_tile, w_tile = c["FETCH_SIZE"], c["WRITE_SIZE"]
-        f_copy = max(found["D"][0]["copy"]["FETCH_SIZE"].values())
-        w_copy = max(found["E"][0]["copy"]["WRITE_SIZE"].values())
+        # the calibration copy is the first device copy of the run (the inputs are drawn after it)
+        first = lambda per: per[min(per, key=int)]
+        f_copy = first(found["D"][0]["copy"]["FETCH_SIZE"])
+        w_copy = first(found["E"][0]["copy"]["WRITE_SIZE"])
         f_scale, w_scale = CAL_BYTES / f_copy, CAL_BYTES / w_copy
         traffic = {"fetch_counter": f_tile, "write_counter": w_tile, "copy_fetch_counter": f_copy, "copy_write_counter": w_copy,
                    "fetch_bytes": f_tile * f_scale, "write_bytes": w_tile * w_scale,
@@ -243,6 +253,136 @@ def summarise(args):
     return 0
 
 
+TRACE_RUNS = {
+    # the timed step of the headline workload and nothing else: every launch of the tile kernel is a launch of that step
+    "step": ["--step-only", "1", "--steps", "10", "--warmup", "2"],
+    # the headline workload with everything bench.py times beside the step
+    "headline": ["--configs", "none"],
+}
+
+
+def trace_command(outdir, run):
+    return ["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", os.path.join(outdir, f"trace_{run}"), "--",
+            "python3", "bench.py"] + TRACE_RUNS[run]
+
+
+def trace(args):
+    """Per-kernel times of bench.py runs: collect (unless --no-run) and write profiles/bench_kernel_trace.md."""
+    lines = ["# Kernel times of bench.py runs (rocprofv3 --kernel-trace --stats)", "",
+             "Kernels of this library (`rc::`) and the device copies; the rest of a run is torch's input generation.  "
+             "Commands from the repository root, after `cd /tmp && export TMPDIR=/tmp`."]
+    for run in args.runs:
+        d = os.path.join(args.dir, f"trace_{run}")
+        if not args.no_run:
+            subprocess.call(["rm", "-rf", d])
+            cmd = ["timeout", "-s", "KILL", str(args.timeout)] + trace_command(args.dir, run)
+            print("[profsum] " + " ".join(cmd), flush=True)
+            with open(d + ".json", "w") as out, open(d + ".err", "w") as err:
+                rc = subprocess.call(cmd, cwd=ROOT, env=dict(os.environ, TMPDIR="/tmp"), stdout=out, stderr=err)
+            if rc != 0:
+                print(f"[profsum] trace failed with status {rc}", flush=True)
+                sys.stdout.write(open(d + ".err").read()[-2000:])
+                return rc
+            for f in glob.glob(os.path.join(d, "*", "*_kernel_trace.csv")):
+                os.remove(f)     # per-dispatch rows of every torch kernel: large, and the stats file has what is kept
+        files = sorted(glob.glob(os.path.join(d, "*", "*_kernel_stats.csv")), key=os.path.getmtime, reverse=True)
+        if not files:
+            print(f"[profsum] no kernel stats under {d}", file=sys.stderr)
+            return 1
+        rows = list(csv.DictReader(open(files[0])))
+        bench = None
+        try:
+            with open(d + ".json") as f:
+                for ln in f:
+                    if ln.startswith("{"):
+                        bench = json.loads(ln)
+        except (OSError, ValueError):
+            pass
+        lines += ["", f"## `bench.py {' '.join(TRACE_RUNS[run])}`", "", "```", " ".join(trace_command("gpurun_out", run)), "```", "",
+                  "| kernel | calls | average, ms | total, ms | share of GPU time |", "|---|---|---|---|---|"]
+        for r in rows:
+            name = r["Name"]
+            if "rc::" not in name and COPY_KERNEL not in name:
+                continue
+            short = name.replace("(anonymous namespace)::", "")
+            short = short[:short.index("(")] if "(" in short else short
+            lines.append(f"| `{short}` | {r['Calls']} | {float(r['AverageNs']) / 1e6:.4f} | {float(r['TotalDurationNs']) / 1e6:.2f} | "
+                         f"{float(r['Percentage']):.2f} % |")
+        if bench and run == "step":
+            k = bench["kernels"]["rc_match_blocks"]
+            flop = bench["roofline"]["algorithmic_flop"]
+            tile = next((r for r in rows if TILE_KERNEL in r["Name"]), None)
+            lines += ["", f"`bench.py` timed `rc_match_blocks` of {bench['config']['workload']} with events at **{k['ms']:.3f} ms** per call in "
+                      "this run (the tile kernel, the clearing of its schedule words and the selection kernel after it)"
+                      + (f"; the profiler's average for the tile kernel is **{float(tile['AverageNs']) / 1e6:.3f} ms** over {tile['Calls']} "
+                         f"launches, i.e. {flop / float(tile['AverageNs']) / 1e3:.0f} TFLOP/s." if tile else ".")]
+    os.makedirs(args.out, exist_ok=True)
+    path = os.path.join(args.out, "bench_kernel_trace.md")
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print(f"[profsum] wrote {path}")
+    return 0
+
+
+def table(args):
+    """profiles/bench_all_workloads.md from the JSON line of one default bench.py run."""
+    bench = None
+    with open(args.json) as f:
+        for ln in f:
+            if ln.startswith("{"):
+                bench = json.loads(ln)
+    if not bench:
+        print(f"[profsum] no JSON line in {args.json}", file=sys.stderr)
+        return 1
+    lines = ["# `bench.py` on the five workloads (one MI355X, one run)", "",
+             "Command (from the repository root): `python3 bench.py` (2 warm-up steps, 10 timed steps per workload; the "
+             "headline is cfg4).  A step = `rc_block_norms`(queries) + `rc_match_blocks` + `rc_remap_block_table` on all "
+             "layers with the pool norms cached; pairs/s = L x P x Q / step time.  The roofline columns are the tile kernel "
+             "inside `rc_match_blocks`, timed with events inside the run; `traffic` is what leaves the L2 per launch "
+             "(`profiles/hbm_traffic.json`) over the KV bytes the launch has to read once.", "",
+             "| workload | L x P x Q, dtype, mode | step, ms | pairs/s | binding roof | of that roof | TFLOP/s (of 2500) | KV GB/s (of 8000) "
+             "| of the pure-MFMA rate this box sustains | traffic / algorithmic | query norms GB/s | remap, us | CPU oracle pairs/s (threads) |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    for name, b in bench["configs"].items():
+        c, r, k = b["config"], b["roofline"], b["kernels"]
+        cpu = b.get("cpu_baseline") or {}
+        ceil = r.get("ceiling", {})
+        tr = r.get("traffic")
+        lines.append(
+            f"| {name} | {c['layers']} x {c['pool_blocks_per_layer']} x {c['query_blocks_per_layer']}, {b['dtype']}, {c['mode']} "
+            f"| {b['ms_per_step']:.3f} | {b['value']:.3g} | {r['bound']} | {r['frac']:.3f} | {r['tflops']:.0f} ({r['mfma_frac']:.3f}) "
+            f"| {r['gb_per_s']:.0f} ({r['hbm_frac']:.3f}) | {ceil.get('frac_of_ceiling', float('nan')):.3f} "
+            f"| {(tr / r['algorithmic_bytes']) if tr else float('nan'):.2f} | {k['rc_block_norms(queries)']['gb_per_s']:.0f} "
+            f"| {k['rc_remap_block_table']['ms'] * 1e3:.0f} | {cpu.get('value', float('nan')):.3g} ({cpu.get('cores', '-')}) |")
+    ceil = bench["roofline"].get("ceiling")
+    if ceil:
+        lines += ["", f"Pure-MFMA rate of this box in the same run: {ceil['pure_mfma_tflops']:.0f} TFLOP/s "
+                  f"({ceil['what']}), i.e. a clock of {ceil['implied_clock_ghz']:.2f} GHz under matrix load."]
+    lines += ["", f"Entry points timed beside the step on {bench['config']['workload']} (`kernels` of the same JSON line):", "",
+              "| entry point | ms | figures |", "|---|---|---|"]
+    for name, k in bench["kernels"].items():
+        rest = ", ".join(f"{a} {b:.4g}" if isinstance(b, float) else f"{a} {b}" for a, b in k.items() if a not in ("ms", "sweep"))
+        lines.append(f"| `{name}` | {k['ms']:.4f} | {rest} |")
+    sweep = bench["kernels"]["rc_remap_block_table"].get("sweep")
+    if sweep:
+        lines += ["", "`rc_remap_block_table` on the table shape of cfg4 at growing layer counts, beside a device copy of the same bytes:", "",
+                  "| layers | bytes | remap, ms | GB/s (of 8000) | copy, ms | remap rate / copy rate |", "|---|---|---|---|---|---|"]
+        for e in sweep:
+            lines.append(f"| {e['layers']} | {e['bytes']:.4g} | {e['ms']:.4f} | {e['gb_per_s']:.0f} ({e['hbm_frac']:.3f}) | "
+                         f"{e['copy_same_bytes_ms']:.4f} | {e['frac_of_copy']:.3f} |")
+    st = bench.get("streaming")
+    if st:
+        lines += ["", f"Steady-state loop ({st['what']}), pool {st['pool']}: {st['ms_per_step']:.2f} ms per step, "
+                  f"{st['pairs_per_s']:.3g} pairs/s; per step {st['shared_per_step']} blocks shared, {st['evicted_per_step']} evicted, "
+                  f"{st['admitted_per_step']} admitted."]
+    os.makedirs(args.out, exist_ok=True)
+    path = os.path.join(args.out, "bench_all_workloads.md")
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print(f"[profsum] wrote {path}")
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -255,8 +395,17 @@ def main():
     b.add_argument("--workload", type=int, required=True)
     b.add_argument("--dir", default="gpurun_out")
     b.add_argument("--out", default="profiles")
+    t = sub.add_parser("trace")
+    t.add_argument("--runs", nargs="+", default=list(TRACE_RUNS), choices=list(TRACE_RUNS))
+    t.add_argument("--dir", default="gpurun_out")
+    t.add_argument("--out", default="profiles")
+    t.add_argument("--timeout", type=int, default=600)
+    t.add_argument("--no-run", action="store_true", help="summarise what an earlier run left under --dir")
+    u = sub.add_parser("table")
+    u.add_argument("--json", required=True, help="file holding the JSON line of a default bench.py run")
+    u.add_argument("--out", default="profiles")
     args = ap.parse_args()
-    sys.exit(collect(args) if args.cmd == "collect" else summarise(args))
+    sys.exit({"collect": collect, "summarise": summarise, "trace": trace, "table": table}[args.cmd](args))
 
 
 if __name__ == "__main__":
