@@ -40,13 +40,15 @@ constexpr int kFinalThreads = 1024;
 constexpr int kFinalPerThread = kMaxQ / kFinalThreads;
 constexpr int kClaimSlots = 4096;
 
-// Workgroups per layer.  One (which then also finalizes its layer) when the layer's table is a few
-// batches or when the layers alone fill the chip; otherwise enough chunks of whole batches for
-// about 256 workgroups.
+// Workgroups per layer.  One (which then also finalizes its layer) when the layers alone fill the chip or the
+// layer's table is small; otherwise as many as keep the launch at one workgroup per compute unit, of at least
+// a quarter batch each: the second launch that adds their histograms costs less than what a single compute
+// unit takes to stream a large layer (measured at 64 layers of 49 664 entries and 50 176 reference counts:
+// 40 us with one workgroup per layer, 30 with 3, 26 with 4, 33 with 8).
 inline int64_t chunks_per_layer(int64_t RE, int64_t L) {
-  if (L >= 128 || RE <= 4 * (int64_t)kGatherBatch) return 1;
-  int64_t g = (256 + L - 1) / (L > 0 ? L : 1);
-  const int64_t most = RE / kGatherBatch;
+  if (L >= 128) return 1;
+  int64_t g = 256 / (L > 0 ? L : 1);
+  const int64_t most = RE / (kGatherBatch / 4);
   if (g > most) g = most;
   if (g < 1) g = 1;
   if (g > 65535) g = 65535;

@@ -99,8 +99,8 @@ def test_remap_validation(lib):
                          kw.get("ws", FAKE), kw.get("wsb", 1 << 20), None]
     need = lib.rc_remap_workspace_size(2, 4, 8, 4, 20)
     assert need == 20 * 4                           # the reverse index; one workgroup per layer keeps its counts in LDS
-    # a layer of 800 000 entries is cut into 48 chunks of whole batches: one histogram of Q counts per chunk and layer
-    assert lib.rc_remap_workspace_size(2, 8, 100000, 4, 20) == 20 * 4 + 2 * 48 * 4 * 4
+    # two layers of 800 000 entries are cut into 128 chunks each (256 workgroups): one histogram of Q counts per chunk and layer
+    assert lib.rc_remap_workspace_size(2, 8, 100000, 4, 20) == 20 * 4 + 2 * 128 * 4 * 4
     assert lib.rc_remap_block_table(*args(L=0)) == 0
     assert lib.rc_remap_block_table(*args(wsb=need - 1)) == 3
     assert lib.rc_remap_block_table(*args(Q=8193)) == 2
