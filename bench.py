@@ -297,6 +297,17 @@ def run_extras(args, w, pr, kernels, s):
             "kv_gb_per_s": kv_bytes / (lm_ms * 1e-3) / 1e9, "workspace_bytes": ws_lm.numel(),
             "matched_blocks": int((lm["match_idx"] >= 0).sum().item())}
         del ws_lm, lm
+        if L > 1:
+            # the same search called for one layer (few tiles: every tile's reduction is split over several workgroups)
+            one = [pr[n][:1] for n in ("kq", "vq", "kp", "vp")]
+            ws1 = torch.empty(max(16, rc.rc_layer_mean_workspace_size(one[0], Q, P)), dtype=torch.uint8, device=dev)
+            lm1 = rc.rc_match_blocks_layer_mean(one[0], one[1], qk[:1], qv[:1], one[2], one[3], pk[:1], pv[:1], lv, 0.5,
+                                                workspace=ws1)
+            lm1_ms = timed(torch, lambda: rc.rc_match_blocks_layer_mean(one[0], one[1], qk[:1], qv[:1], one[2], one[3], pk[:1],
+                                                                        pv[:1], lv, 0.5, workspace=ws1, out=lm1), args.steps)
+            kernels["rc_match_blocks_layer_mean(one layer per call, not in the step)"] = {
+                "ms": lm1_ms, "tflops": flop / L / (lm1_ms * 1e-3) / 1e12, "workspace_bytes": ws1.numel()}
+            del ws1, lm1
     if args.pat_samples > 0:
         # percentile threshold over a warm-up sample of this many distances (not part of the step)
         n = args.pat_samples

@@ -80,6 +80,7 @@ struct MatchParams {
   int rounds;      // slots in one workgroup's walk
   int dyn_from;    // slots from this one on can be taken from the back of their list
   int steal_min;   // a slot is taken from a list's back only if its own workgroup is at least this far short of it
+  int raw;    // MODE 3: the shares hold the bare dot products (the layer-mean distance is formed from their sums)
   int chunk;  // tiles handed to one XCD in a row
   int G;      // layer-mean mode: layers per group (one workgroup walks the layers of its group)
   int S;      // split mode: workgroups per tile, each over its own part of the reduction (even)
@@ -830,7 +831,9 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             // fq fp = aVq aVp / 2; rq rp = (aKq aKp) / (aVq aVp); in MODE 4 the K part was rescaled at the phase end
-            const float f = (MODE == 4 || split_v) ? fq[j] * rs.fp[g][e] : (rq[j] * fq[j]) * (rs.rp[g][e] * rs.fp[g][e]);
+            const float f = (MODE == 3 && p.raw)      ? 1.f
+                            : (MODE == 4 || split_v) ? fq[j] * rs.fp[g][e]
+                                                     : (rq[j] * fq[j]) * (rs.rp[g][e] * rs.fp[g][e]);
             d[e] = acc[i][j][4 * g + e] * f;
           }
           out[((i * 4 + g) * TQ + j) * 64] = d;
@@ -1020,6 +1023,67 @@ __global__ __launch_bounds__(256) void tile_sums_select_kernel(const float* __re
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (r + e < pend && (!live || live[r + e])) top2_push(-(sum[e] * scale), r + e, best, bidx, second);
+    }
+  }
+  Part t;
+  t.best = best;
+  t.idx = bidx;
+  t.second = second;
+  t.pad = 0;
+  s_part[tp][tq] = t;
+  __syncthreads();
+  if (tp == 0 && q < Q) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const Part u = s_part[w][tq];
+      top2_merge(t.best, t.idx, t.second, u.best, u.idx, u.second);
+    }
+    part[(long long)blockIdx.y * Q + q] = t;
+  }
+}
+
+// Layer-mean distance from the shares of a split reduction (few tiles: every tile's reduction was cut into
+// `shares` workgroups, the first half on the K tensor, the second on V, each storing its bare partial dot
+// products as a tile in register order, laid out [layer][share][pool tile][query tile]).  Per pair and layer the
+// shares of each tensor are added in ascending order, |x - y| = sqrt(max(|x|^2 + |y|^2 - 2 x.y, 0)) is formed
+// from the cached squared norms exactly as the whole-tile path folds it, the layers are added in ascending
+// order, and the selection is the one of tile_sums_select_kernel (top-2 on -distance, dead and tail rows out).
+__global__ __launch_bounds__(256) void layer_mean_shares_select_kernel(
+    const float* __restrict__ dpart, int shares, int L, int P, int Q, int npt, int nqt, int sel_rows, float scale,
+    const uint8_t* __restrict__ live, const float* __restrict__ q_ksq, const float* __restrict__ q_vsq,
+    const float* __restrict__ p_ksq, const float* __restrict__ p_vsq, Part* __restrict__ part) {
+  __shared__ Part s_part[4][64];
+  const int tq = threadIdx.x & 63, tp = threadIdx.x >> 6;
+  const int q = blockIdx.x * 64 + tq;
+  const int pbeg = blockIdx.y * sel_rows, pend = min(P, pbeg + sel_rows);
+  const long long gstride = (long long)npt * nqt * 65536;
+  float best = -INFINITY, second = -INFINITY;
+  int bidx = -1;
+  if (q < Q) {
+    for (int r = pbeg + 4 * tp; r < pend; r += 16) {
+      const float* src = dpart + ((long long)(r >> 8) * nqt + (q >> 8)) * 65536 + sum_index(r & 255, q & 255);
+      f32x4 dist = {0.f, 0.f, 0.f, 0.f};
+      for (int l = 0; l < L; ++l) {
+        const float* lsrc = src + (long long)l * shares * gstride;
+        f32x4 dot[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          dot[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int g = 0; g < shares / 2; ++g)
+            dot[t] += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(lsrc + (long long)(t * (shares / 2) + g) * gstride));
+        }
+        const float nqk = q_ksq[(long long)l * Q + q], nqv = q_vsq[(long long)l * Q + q];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (r + e >= pend) continue;
+          const float npk = p_ksq[(long long)l * P + r + e], npv = p_vsq[(long long)l * P + r + e];
+          dist[e] += __builtin_amdgcn_sqrtf(fmaxf(fmaf(-2.f, dot[0][e], nqk + npk), 0.f));
+          dist[e] += __builtin_amdgcn_sqrtf(fmaxf(fmaf(-2.f, dot[1][e], nqv + npv), 0.f));
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (r + e < pend && (!live || live[r + e])) top2_push(-(dist[e] * scale), r + e, best, bidx, second);
     }
   }
   Part t;
@@ -1335,6 +1399,7 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.nqt = (int)sl.nqt;
     mp.total = (int)(L * sl.npt * sl.nqt * S);
     mp.chunk = kChunk;
+    mp.raw = 0;
     mp.G = 1;
     mp.S = S;
     mp.stagger_wgs = 0;
@@ -1391,6 +1456,7 @@ extern "C" rc_status rc_match_blocks(const rc_kv_desc* qdesc, const rc_kv_desc* 
     mp.nqt = (int)nqt;
     mp.total = (int)total;
     mp.chunk = kChunk;
+    mp.raw = 0;
     mp.dpart = nullptr;
     mp.G = 1;
     mp.S = 1;
@@ -1415,6 +1481,8 @@ extern "C" size_t rc_layer_mean_workspace_size(const rc_kv_desc* qdesc, int64_t 
   using namespace rc;
   if (!qdesc || Q < 0 || P < 0 || qdesc->n_layers <= 0) return 0;
   const int64_t npt = (P + kBlockTile.bp - 1) / kBlockTile.bp, nqt = (Q + kBlockTile.bq - 1) / kBlockTile.bq;
+  const int S = split_count(RC_SCORE_BLOCK, qdesc->n_layers, P, Q, qdesc->block_tokens, qdesc->n_kv_heads);
+  if (S > 1) return split_layout(S, qdesc->n_layers, P, Q).bytes;  // few tiles: shares of every tile's reduction
   const LayerSplit ls = layer_split(qdesc->n_layers, npt * nqt);
   const int sel_rows = select_rows(P, Q);
   const int64_t nchunks = (P + sel_rows - 1) / sel_rows;
@@ -1457,6 +1525,62 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
                 need, workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   float* dpart = static_cast<float*>(workspace);
+  const float scale = 1.0f / ((float)L * 2.0f * (float)qdesc->block_tokens * (float)qdesc->n_kv_heads);
+  const int S = split_count(RC_SCORE_BLOCK, L, P, Q, qdesc->block_tokens, qdesc->n_kv_heads);
+  if (S > 1) {
+    // Few tiles (a call with one or a few layers, a small pool): the launch would leave compute units idle, and
+    // giving every workgroup fewer layers does not help below one layer each.  Every tile's reduction is cut into
+    // S shares as in rc_match_blocks (half of them on K, half on V), the shares store bare dot products, and the
+    // selection kernel forms the distances from their sums.
+    const SplitLayout sl = split_layout(S, L, P, Q);
+    MatchParams mp;
+    mp.kq = static_cast<const char*>(kq);
+    mp.vq = static_cast<const char*>(vq);
+    mp.kp = static_cast<const char*>(kp);
+    mp.vp = static_cast<const char*>(vp);
+    mp.q_ksq = q_ksq;
+    mp.q_vsq = q_vsq;
+    mp.p_ksq = p_ksq;
+    mp.p_vsq = p_vsq;
+    mp.live = nullptr;
+    mp.part = nullptr;
+    mp.dpart = dpart;
+    mp.q_lstride_b = qdesc->layer_stride * 2;
+    mp.p_lstride_b = pdesc->layer_stride * 2;
+    mp.L = L;
+    mp.Q = (int)Q;
+    mp.P = (int)P;
+    mp.T = qdesc->block_tokens;
+    mp.H = qdesc->n_kv_heads;
+    mp.npt = (int)sl.npt;
+    mp.nqt = (int)sl.nqt;
+    mp.total = (int)(L * sl.npt * sl.nqt * S);
+    mp.chunk = kChunk;
+    mp.raw = 1;
+    mp.G = 1;
+    mp.S = S;
+    mp.stagger_wgs = 0;
+    mp.stagger_unit = 0;
+    mp.vgrid = (int)virtual_grid(mp.total);
+    const unsigned grid = launch_grid((unsigned)mp.vgrid);
+    mp.ctr = nullptr;
+    mp.rounds = 0;
+    mp.steal_min = 0;
+    mp.dyn_from = 0;
+    if (qdesc->dtype == RC_BF16)
+      match_tile_kernel<true, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
+    else
+      match_tile_kernel<false, 256, 256, 3><<<grid, kThreads, 0, st>>>(mp);
+    if (rc_status s = check_launch("rc_match_blocks_layer_mean(tile shares)")) return s;
+    Part* part = reinterpret_cast<Part*>(static_cast<char*>(workspace) + sl.part_offset);
+    const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)sl.nchunks);
+    layer_mean_shares_select_kernel<<<sgrid, 256, 0, st>>>(dpart, S, L, (int)P, (int)Q, (int)sl.npt, (int)sl.nqt, sl.sel_rows,
+                                                           scale, pool_live, q_ksq, q_vsq, p_ksq, p_vsq, part);
+    if (rc_status s = check_launch("rc_match_blocks_layer_mean(select)")) return s;
+    layer_mean_finalize_kernel<<<(unsigned)((Q + 63) / 64), 256, 0, st>>>(part, (int)sl.nchunks, (int)Q, threshold, best_idx,
+                                                                          best_dist, match_idx, second_dist);
+    return check_launch("rc_match_blocks_layer_mean(finalize)");
+  }
   Part* part = reinterpret_cast<Part*>(static_cast<char*>(workspace) + layer_mean_part_offset(ls.groups, npt, nqt));
   const int sel_rows = select_rows(P, Q);
   const int64_t nchunks = (P + sel_rows - 1) / sel_rows;
@@ -1484,6 +1608,7 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     mp.nqt = (int)nqt;
     mp.total = (int)total;
     mp.chunk = kChunk;
+    mp.raw = 0;
     mp.G = ls.G;
     mp.S = 1;
     mp.stagger_wgs = compute_units();
@@ -1496,7 +1621,6 @@ extern "C" rc_status rc_match_blocks_layer_mean(const rc_kv_desc* qdesc, const r
     else
       match_tile_kernel<false, kBlockTile.bp, kBlockTile.bq, 2><<<grid, kThreads, 0, st>>>(mp);
     if (rc_status s = check_launch("rc_match_blocks_layer_mean(tiles)")) return s;
-    const float scale = 1.0f / ((float)L * 2.0f * (float)qdesc->block_tokens * (float)qdesc->n_kv_heads);
     const dim3 sgrid((unsigned)((Q + 63) / 64), (unsigned)nchunks);
     tile_sums_select_kernel<<<sgrid, 256, 0, st>>>(dpart, ls.groups, (int)P, (int)Q, (int)npt, (int)nqt, sel_rows, scale, 0,
                                                     pool_live, part);
