@@ -423,7 +423,11 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     move_cursor(f);
     next_stage(f, stages);
   };
-  auto dmaA = [&](int i) { dma16<true>(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16); };
+  // The pool loads carry the non-temporal hint except in the layer-mean mode: there the workgroups that share a
+  // pool tile leave a fold (a read-modify-write of 256 KB each) a few microseconds apart, and a line that is not
+  // kept is gone before the last of them asks for it (measured: twice the L2-out traffic of the cosine mode
+  // with the hint, and 6 % of the launch).
+  auto dmaA = [&](int i) { dma16<MODE != 2>(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16); };
   auto dmaB = [&](int i) { dma16<false>(fb.srd, voff, fb.off + i * load_stride, fb.dst + i * NT * 16); };
 
   f32x16 acc[TP][TQ];
