@@ -181,7 +181,8 @@ struct Cursor {
 // over its elements, as a 256x256 tile of floats; a second kernel adds the S shares and selects.
 // MODE 4 = the same for the per-head-all score: S = H shares, share h computes the score of head h
 // over the head's K and V slices, and the second kernel takes the minimum over the shares.
-template <bool BF16, int BP, int BQ, int MODE>
+// SHARED_POOL: several query tiles, i.e. several workgroups read every pool slice (see the pool loads below).
+template <bool BF16, int BP, int BQ, int MODE, bool SHARED_POOL = false>
 __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
   constexpr int NT = kThreads, WP = kPoolWaves, WQ = kQueryWaves;
@@ -423,11 +424,17 @@ __global__ __launch_bounds__(kThreads, 1) void match_tile_kernel(const MatchPara
     move_cursor(f);
     next_stage(f, stages);
   };
-  // The pool loads carry the non-temporal hint except in the layer-mean mode: there the workgroups that share a
-  // pool tile leave a fold (a read-modify-write of 256 KB each) a few microseconds apart, and a line that is not
-  // kept is gone before the last of them asks for it (measured: twice the L2-out traffic of the cosine mode
-  // with the hint, and 6 % of the launch).
-  auto dmaA = [&](int i) { dma16<MODE != 2>(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16); };
+  // The pool loads carry the non-temporal hint when nobody else reads the slice (one query tile, cfg2: 8 % less
+  // launch time than without it, since the slice then does not displace the query slices that every pool tile
+  // of the layer re-reads from the L2).  With several query tiles the workgroups that share a pool tile want to
+  // find each other's slice in the L2, and a line that is not kept can be gone before the last of them asks for
+  // it: 0.5-1.4 % on the Q = 1024 workloads, and in the layer-mean mode, where those workgroups leave a fold
+  // (a read-modify-write of 256 KB each) a few microseconds apart, twice the L2-out traffic and 6 % of the
+  // launch.  The cosine mode is compiled in both forms, the layer-mean mode without the hint; the per-head and
+  // the few-tiles modes keep it (measured: no difference there).
+  auto dmaA = [&](int i) {
+    dma16<MODE != 2 && !SHARED_POOL>(fa.srd, voff, fa.off + i * load_stride, fa.dst + i * NT * 16);
+  };
   auto dmaB = [&](int i) { dma16<false>(fb.srd, voff, fb.off + i * load_stride, fb.dst + i * NT * 16); };
 
   f32x16 acc[TP][TQ];
@@ -1319,6 +1326,8 @@ void launch_tiles(int mode, const MatchParams& mp, unsigned grid, hipStream_t st
     match_tile_kernel<BF16, kNarrowTile.bp, kNarrowTile.bq, 0><<<grid, kThreads, 0, st>>>(mp);
   else if (mode == RC_SCORE_BLOCK && mp.Q <= kMidTile.bq)
     match_tile_kernel<BF16, kMidTile.bp, kMidTile.bq, 0><<<grid, kThreads, 0, st>>>(mp);
+  else if (mode == RC_SCORE_BLOCK && mp.nqt > 1)
+    match_tile_kernel<BF16, kBlockTile.bp, kBlockTile.bq, 0, true><<<grid, kThreads, 0, st>>>(mp);
   else if (mode == RC_SCORE_BLOCK)
     match_tile_kernel<BF16, kBlockTile.bp, kBlockTile.bq, 0><<<grid, kThreads, 0, st>>>(mp);
   else
