@@ -1,9 +1,9 @@
 """Profiler passes over ``bench.py`` and the short summaries kept under ``profiles/``.
 
-    python3 -m paper_2507_21433_amd.profsum collect --workload 4 --passes A B C D E --dir gpurun_out
-    python3 -m paper_2507_21433_amd.profsum summarise --workload 4 --dir gpurun_out --out profiles
-    python3 -m paper_2507_21433_amd.profsum trace --dir gpurun_out --out profiles
-    python3 -m paper_2507_21433_amd.profsum table --json gpurun_out/bench.json --out profiles
+    python3 -m paper_2507_21433_amd.profsum collect --workload 4 --passes A B C D E
+    python3 -m paper_2507_21433_amd.profsum summarise --workload 4 --out profiles
+    python3 -m paper_2507_21433_amd.profsum trace --out profiles
+    python3 -m paper_2507_21433_amd.profsum table --json bench.json --out profiles
 
 ``collect`` runs, once per pass, ``rocprofv3 --pmc <counters of the pass> --kernel-trace --output-format csv
 -d <dir>/pmc_w<N>_<pass> -- python3 bench.py --step-only 1 --workload N --steps 3 --warmup 1`` (one pass per run: the
@@ -151,7 +151,7 @@ def summarise(args):
               "made with `python3 -m paper_2507_21433_amd.profsum collect` and condensed with its `summarise`.", ""]
     lines += ["Commands (from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", "", "```"]
     for name in found:
-        lines.append(" ".join(pass_command(wl, name, "gpurun_out")))
+        lines.append(" ".join(pass_command(wl, name, args.dir)))
     lines += ["```", ""]
     if bench:
         lines += [f"`bench.py`'s own event timing of the launch during pass {next(iter(found))} (counters being collected): "
@@ -222,7 +222,7 @@ def summarise(args):
         traffic = {"fetch_counter": f_tile, "write_counter": w_tile, "copy_fetch_counter": f_copy, "copy_write_counter": w_copy,
                    "fetch_bytes": f_tile * f_scale, "write_bytes": w_tile * w_scale,
                    "hbm_bytes_per_launch": f_tile * f_scale + w_tile * w_scale, "algorithmic_bytes": alg_bytes,
-                   "commands": [" ".join(pass_command(wl, n, "gpurun_out")) for n in ("D", "E")]}
+                   "commands": [" ".join(pass_command(wl, n, args.dir)) for n in ("D", "E")]}
         lines.append(f"- HBM traffic: FETCH_SIZE {f_tile:.6g} and WRITE_SIZE {w_tile:.6g} per launch; the 1 GiB copy of the same runs "
                      f"reads {f_copy:.6g} and writes {w_copy:.6g}, so one count is {f_scale:.1f} bytes fetched, {w_scale:.1f} bytes "
                      f"written: **{traffic['fetch_bytes'] / 1e9:.2f} GB read + {traffic['write_bytes'] / 1e9:.3f} GB written per launch**"
@@ -298,7 +298,7 @@ def trace(args):
                         bench = json.loads(ln)
         except (OSError, ValueError):
             pass
-        lines += ["", f"## `bench.py {' '.join(TRACE_RUNS[run])}`", "", "```", " ".join(trace_command("gpurun_out", run)), "```", "",
+        lines += ["", f"## `bench.py {' '.join(TRACE_RUNS[run])}`", "", "```", " ".join(trace_command(args.dir, run)), "```", "",
                   "| kernel | calls | average, ms | total, ms | share of GPU time |", "|---|---|---|---|---|"]
         for r in rows:
             name = r["Name"]
@@ -389,15 +389,15 @@ def main():
     a = sub.add_parser("collect")
     a.add_argument("--workload", type=int, required=True)
     a.add_argument("--passes", nargs="+", default=list(PASSES), choices=list(PASSES))
-    a.add_argument("--dir", default="gpurun_out")
+    a.add_argument("--dir", default="prof_raw", help="directory of the raw profiler output")
     a.add_argument("--timeout", type=int, default=240, help="seconds per pass")
     b = sub.add_parser("summarise")
     b.add_argument("--workload", type=int, required=True)
-    b.add_argument("--dir", default="gpurun_out")
+    b.add_argument("--dir", default="prof_raw", help="directory of the raw profiler output")
     b.add_argument("--out", default="profiles")
     t = sub.add_parser("trace")
     t.add_argument("--runs", nargs="+", default=list(TRACE_RUNS), choices=list(TRACE_RUNS))
-    t.add_argument("--dir", default="gpurun_out")
+    t.add_argument("--dir", default="prof_raw", help="directory of the raw profiler output")
     t.add_argument("--out", default="profiles")
     t.add_argument("--timeout", type=int, default=600)
     t.add_argument("--no-run", action="store_true", help="summarise what an earlier run left under --dir")
