@@ -128,14 +128,15 @@ def test_match_many_layers_whole_tiles(oracle, L, P, Q):
     assert (gpu["best_idx"][:, 0] == 1).all() and (gpu["match_idx"][:, 0] == 1).all()
 
 
-def test_match_many_rounds_tiles_change_hands(oracle):
+@pytest.mark.parametrize("mode,H", [(0, 1), (1, 2)])
+def test_match_many_rounds_tiles_change_hands(oracle, mode, H):
     # 16 rounds of tiles and more: the last tenth of every XCD's list of tiles can be taken over by the workgroups of
     # the XCDs that are through with theirs.  Every tile must still be computed exactly once: the call equals, bit
     # for bit, the same layers scored 20 at a time (two rounds, the fixed schedule), and sampled queries equal the
     # oracle's search.
     L, P, Q = 260, 513, 1300
-    w = synth.scaled(synth.WORKLOADS[2], name=f"many_rounds_L{L}_{P}x{Q}", L=L, P=P, Q=Q, H=1, planted_frac=0.3, R=1,
-                     E=P + Q, seed=21)
+    w = synth.scaled(synth.WORKLOADS[2 if mode == 0 else 5], name=f"many_rounds_mode{mode}_L{L}_{P}x{Q}", L=L, P=P, Q=Q,
+                     T=16, H=H, planted_frac=0.3, R=1, E=P + Q, seed=21)
     say(w.name)
     pr = synth.make_problem(w, DEV)
     live = pr["live"].clone()
