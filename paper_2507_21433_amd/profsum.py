@@ -258,6 +258,9 @@ TRACE_RUNS = {
     "step": ["--step-only", "1", "--steps", "10", "--warmup", "2"],
     # the headline workload with everything bench.py times beside the step
     "headline": ["--configs", "none"],
+    # the default run: all five workloads (instantiations of the tile kernel are shared between workloads and with
+    # the one-layer-per-call side measurement, so their averages mix shapes)
+    "default": [],
 }
 
 
@@ -308,6 +311,11 @@ def trace(args):
             short = short[:short.index("(")] if "(" in short else short
             lines.append(f"| `{short}` | {r['Calls']} | {float(r['AverageNs']) / 1e6:.4f} | {float(r['TotalDurationNs']) / 1e6:.2f} | "
                          f"{float(r['Percentage']):.2f} % |")
+        if run != "step":
+            lines += ["", "In this run the tile kernel instantiation of the headline workload is launched by the timed step and "
+                      "by the one-layer-per-call side measurement (a launch of one layer's tiles, 1/64 of the work), and the "
+                      "layer-mean instantiation by its own measurement and by the steady-state loop: their averages mix "
+                      "shapes.  The run of the timed step alone, above, is the one whose average is a launch of the step."]
         if bench and run == "step":
             k = bench["kernels"]["rc_match_blocks"]
             flop = bench["roofline"]["algorithmic_flop"]
