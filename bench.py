@@ -208,9 +208,15 @@ def run_config(args, w, traffic, extras, cpu_budget):
                                  "hbm_frac": remap_bytes / (remap_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
     }
     streaming = None
+    errors = {}
     if extras:
-        streaming = run_extras(args, w, pr, kernels, dict(qk=qk, qv=qv, pk=pk, pv=pv, out=out, flop=flop, kv_bytes=kv_bytes,
-                                                          pairs=pairs))
+        try:
+            streaming = run_extras(args, w, pr, kernels, dict(qk=qk, qv=qv, pk=pk, pv=pv, out=out, flop=flop, kv_bytes=kv_bytes,
+                                                              pairs=pairs))
+        except Exception as e:   # noqa: BLE001  (the measurements beside the step must not take the step's figures with them)
+            log(f"measurements beside the step failed: {e!r}")
+            errors["measurements beside the step"] = repr(e)
+            torch.cuda.empty_cache()
     matched = int((out["match_idx"] >= 0).sum().item())
     n_remapped = int(res["n_remapped"].sum().item())
 
@@ -232,6 +238,8 @@ def run_config(args, w, traffic, extras, cpu_budget):
     }
     if extras:
         block["streaming"] = streaming
+    if errors:
+        block["side_errors"] = errors
     del pr, pk, pv, qk, qv, ws_match, ws_remap, out, remap_out
     torch.cuda.empty_cache()
     return block
@@ -552,16 +560,31 @@ def main():
     configs = {}
     others = [] if (args.step_only or args.configs.strip().lower() in ("", "none")) else \
         [int(x) for x in args.configs.split(",") if int(x) != args.workload]
+    side_errors = {}
+
+    def guarded(what, fn):
+        """A side measurement that fails must not take the headline with it: its error goes into the JSON line."""
+        try:
+            return fn()
+        except Exception as e:   # noqa: BLE001
+            log(f"{what} failed: {e!r}")
+            side_errors[what] = repr(e)
+            torch.cuda.empty_cache()
+            return None
+
     for n in others:
-        b = run_config(args, workload(n), traffic, extras=False, cpu_budget=args.cpu_pairs / 3)
-        configs[b["config"]["workload"]] = b
+        b = guarded(f"workload {n}", lambda: run_config(args, workload(n), traffic, extras=False, cpu_budget=args.cpu_pairs / 3))
+        if b is not None:
+            configs[b["config"]["workload"]] = b
     head = run_config(args, workload(args.workload), traffic, extras=not args.step_only,
                       cpu_budget=0 if args.step_only else args.cpu_pairs)
     if args.remap_sweep and not args.step_only:
-        head["kernels"]["rc_remap_block_table"]["sweep"] = remap_sweep(args)
+        sweep = guarded("remap sweep", lambda: remap_sweep(args))
+        if sweep is not None:
+            head["kernels"]["rc_remap_block_table"]["sweep"] = sweep
     if not args.step_only:
-        ceiling = mfma_probe()
-        for b in list(configs.values()) + [head]:
+        ceiling = guarded("pure-MFMA probe", mfma_probe)
+        for b in (list(configs.values()) + [head]) if ceiling else []:
             r = b["roofline"]
             r["ceiling"] = dict(ceiling, frac_of_ceiling=r["tflops"] / ceiling["pure_mfma_tflops"])
     brief = {k: head[k] for k in ("value", "unit", "ms_per_step", "dtype", "config", "kv_gb_per_s", "roofline", "cpu_baseline")}
@@ -585,6 +608,8 @@ def main():
     }
     if traffic_note:
         line["traffic_note"] = traffic_note
+    if side_errors or head.get("side_errors"):
+        line["side_errors"] = dict(side_errors, **head.get("side_errors", {}))
     print(json.dumps(line), flush=True)
 
 
